@@ -1,0 +1,160 @@
+/*
+ * loong.h - C ABI of the per-device ring-step attention of Double-Ring-Attention.
+ *
+ * One GPU of a context-parallel group holds a local Q chunk and, at every ring
+ * micro-step, one visiting K/V chunk.  Per micro-step it runs a blockwise softmax
+ * attention of its Q against that chunk and folds the partial result into the running
+ * output with a log-sum-exp update (paper: Alg. 2, the `Attention` and `Update` calls of
+ * the inner loop).  The backward pass replays the chunks and, per micro-step, produces
+ * the visiting chunk's dK/dV and this step's share of dQ from the stored attention
+ * output and softmax_lse (paper: Sec. 3.1 last paragraph; Sec. "Selective Checkpoint++").
+ *
+ * Conventions for every entry point
+ *   - plain C, no exceptions, returns 0 (LOONG_OK) or a negative LOONG_E_* code; the
+ *     text of the last error of the calling thread is at loong_last_error().
+ *   - every tensor pointer is a DEVICE pointer owned by the caller and must stay valid
+ *     until the work enqueued on `stream` has finished; descriptors and the small
+ *     arrays of loong_zigzag_mask are HOST memory read during the call.
+ *   - nothing allocates, frees or synchronises; kernels are enqueued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream).
+ *   - arguments are validated before anything is launched; on error nothing is enqueued.
+ *   - layouts: 16-bit/fp32 inputs q,k,v,o,d_o are [batch, head, token, head_dim] with
+ *     element strides given in the descriptor (head_dim stride 1).  fp32 results `out`
+ *     and `dq` use o_stride; `dk`,`dv` are contiguous [batch, n_kv_heads, kv_len, head_dim];
+ *     `lse` and `delta` are contiguous [batch, n_q_heads, q_len].
+ */
+#ifndef LOONG_H
+#define LOONG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define LOONG_API __attribute__((visibility("default")))
+#else
+#define LOONG_API
+#endif
+
+#define LOONG_OK              0
+#define LOONG_E_NULL         -1   /* a required pointer is NULL */
+#define LOONG_E_SHAPE        -2   /* negative/inconsistent sizes, bad rank/step/cp */
+#define LOONG_E_UNSUPPORTED  -3   /* head_dim, head grouping or size outside the kernels' range */
+#define LOONG_E_ALIGN        -4   /* pointer not 16-byte aligned or stride not vectorisable */
+#define LOONG_E_DTYPE        -5   /* unknown dtype code */
+#define LOONG_E_HIP          -6   /* the HIP runtime refused a launch */
+
+/* storage type of q, k, v, o, d_o */
+#define LOONG_BF16 0              /* bf16 MFMA kernels, head_dim 64 or 128 */
+#define LOONG_FP32 1              /* plain fp32 kernels (small cases), head_dim <= 128, multiple of 4 */
+
+/* class of a (q half, k half) block of one micro-step */
+#define LOONG_SKIP 0              /* key chunk lies after the query chunk: nothing visible */
+#define LOONG_FULL 1              /* key chunk lies before the query chunk: everything visible */
+#define LOONG_DIAG 2              /* same chunk: key offset <= query offset */
+
+/* flags */
+#define LOONG_FUSE_MERGE     1    /* fwd: out/lse hold the running result; the step is merged in-kernel */
+#define LOONG_ACCUM_DKV      2    /* bwd: dk/dv are added to instead of overwritten */
+#define LOONG_COMPUTE_DELTA  4    /* bwd: fill `delta` from o and d_o before the step */
+
+typedef struct loong_step_desc {
+  int32_t batch;
+  int32_t n_q_heads;      /* local q heads; q head h reads kv head h / (n_q_heads / n_kv_heads) */
+  int32_t n_kv_heads;     /* local kv heads (after any replication), divides n_q_heads */
+  int32_t head_dim;
+  int32_t q_len;          /* local q tokens;  causal: 2 * chunk_len */
+  int32_t kv_len;         /* tokens of the visiting chunk; causal: 2 * chunk_len */
+  int32_t chunk_len;      /* causal only: length c of one zigzag half */
+  int32_t q_chunk[2];     /* causal only: global chunk ids of q rows [0,c) and [c,2c) */
+  int32_t kv_chunk[2];    /* causal only: same for the visiting keys */
+  int32_t causal;         /* 0: every key visible to every row (chunk fields ignored) */
+  int32_t dtype;          /* LOONG_BF16 | LOONG_FP32 */
+  float   softmax_scale;  /* multiplies q.k before the softmax (e.g. 1/sqrt(head_dim)) */
+  int32_t flags;
+  int64_t q_stride[3];    /* batch, head, token strides (elements) of q, o and d_o */
+  int64_t kv_stride[3];   /* same for k and v */
+  int64_t o_stride[3];    /* same for the fp32 out and dq */
+} loong_step_desc;
+
+/*
+ * Zigzag layout and ring order (host only, pure).  Paper: Sec. 2 "Distributed Attention"
+ * (load-balanced causal reorder) and Alg. 2 (outer loop of cp/inner_w steps around an
+ * inner loop of inner_w micro-steps; sends go to the next rank, receives come from the
+ * previous).  The sequence is cut into 2*cp chunks; rank r owns chunks r and 2cp-1-r.
+ * Ranks are numbered i*inner_w + j for the j-th GPU of the i-th inner ring.
+ * `step` counts micro-steps 0..cp-1 in execution order.  Outputs (any may be NULL):
+ *   src_rank    rank whose chunk is held at that micro-step
+ *   q_chunk     {rank, 2cp-1-rank};  kv_chunk  {src, 2cp-1-src}
+ *   block_class [qhalf*2 + khalf] in {LOONG_SKIP, LOONG_FULL, LOONG_DIAG}
+ * Errors: LOONG_E_SHAPE if cp < 1, inner_w < 1, cp % inner_w != 0, rank or step out of range.
+ */
+LOONG_API int loong_zigzag_mask(int32_t cp, int32_t inner_w, int32_t rank, int32_t step,
+                      int32_t* src_rank, int32_t q_chunk[2], int32_t kv_chunk[2],
+                      uint8_t block_class[4]);
+
+/*
+ * One micro-step forward: `Attention(Q, K, V)` of Alg. 2, optionally fused with `Update`.
+ * q [B,Hq,q_len,d], k/v [B,Hkv,kv_len,d] in desc->dtype.
+ * Without LOONG_FUSE_MERGE: out <- softmax(scale q k^T + mask) v over this chunk only,
+ * lse <- natural-log sum of exp of the masked scaled scores; rows that see no key get
+ * out = 0, lse = -inf.  With LOONG_FUSE_MERGE: (out, lse) is the running result (start
+ * from out = 0, lse = -inf) and is replaced by its update with this step's partial;
+ * rows that see no key are left untouched.  Fixed order of operations per row:
+ * results are bit-reproducible run to run.
+ */
+LOONG_API int loong_attn_step_fwd(const loong_step_desc* desc, const void* q, const void* k, const void* v,
+                        float* out, float* lse, void* stream);
+
+/*
+ * `Update(out, lse, block_out, block_lse)` of Alg. 2, in place on (out, lse):
+ *   lse' = log(exp(lse) + exp(block_lse)),
+ *   out' = exp(lse - lse') out + exp(block_lse - lse') block_out.
+ * rows = batch*heads*tokens; out/block_out [rows, head_dim] fp32 contiguous, lse/block_lse
+ * [rows].  A side with lse = -inf contributes nothing.  head_dim must be a multiple of 4.
+ */
+LOONG_API int loong_lse_merge(int64_t rows, int32_t head_dim, float* out, float* lse,
+                    const float* block_out, const float* block_lse, void* stream);
+
+/*
+ * One micro-step backward (paper: Sec. 3.1, gradients of the visiting K/V travel with the
+ * chunk; the kernel recomputes the probabilities from the stored softmax_lse).
+ * Inputs: q, d_o [B,Hq,q_len,d] (q_stride), k, v the visiting chunk, lse and delta
+ * [B,Hq,q_len] of the COMPLETE attention (all chunks merged), delta_i = sum_k d_o_ik o_ik.
+ * With LOONG_COMPUTE_DELTA, `o` (stored output, same type/strides as q) must be given and
+ * delta is written first; otherwise `o` may be NULL.
+ * Outputs: dq [B,Hq,q_len,d] fp32 (o_stride) is ADDED to (zero it before the first
+ * step; fp32 atomics: order of additions is not fixed); dk, dv fp32 contiguous
+ * [B,Hkv,kv_len,d] are overwritten, or added to with LOONG_ACCUM_DKV.
+ */
+LOONG_API int loong_attn_step_bwd(const loong_step_desc* desc, const void* q, const void* k, const void* v,
+                        const void* o, const void* d_o, const float* lse, float* delta,
+                        float* dq, float* dk, float* dv, void* stream);
+
+/* delta_i = sum_k d_o_ik * o_ik for every row; o, d_o in desc->dtype with q_stride. */
+LOONG_API int loong_bwd_delta(const loong_step_desc* desc, const void* o, const void* d_o, float* delta,
+                    void* stream);
+
+/* Set a running result to the neutral element of Update: out = 0, lse = -inf. */
+LOONG_API int loong_init_running(int64_t rows, int32_t head_dim, float* out, float* lse, void* stream);
+
+/* Cast the merged fp32 output [rows, head_dim] to the stored activation type
+ * (LOONG_BF16: round to nearest even; LOONG_FP32: copy), contiguous. */
+LOONG_API int loong_finalize_out(int64_t rows, int32_t head_dim, const float* out, void* o, int32_t dtype,
+                       void* stream);
+
+/* Validate a descriptor exactly as the step calls do, without touching a device. */
+LOONG_API int loong_validate_step(const loong_step_desc* desc);
+
+/* Text of the calling thread's last error ("" if none). Never NULL. */
+LOONG_API const char* loong_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+LOONG_API int loong_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOONG_H */

@@ -1,0 +1,44 @@
+// C entry points of the forward and backward micro-step: validate, then dispatch on dtype.
+#include <hip/hip_runtime.h>
+
+#include "loong_internal.h"
+
+using namespace loong;
+
+extern "C" {
+
+int loong_attn_step_fwd(const loong_step_desc* desc, const void* q, const void* k, const void* v,
+                        float* out, float* lse, void* stream) {
+  clear_error();
+  StepGeom g;
+  if (int rc = check_step(desc, &g)) return rc;
+  if (!q || !k || !v || !out || !lse) return fail(LOONG_E_NULL, "loong_attn_step_fwd: NULL tensor");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+    return fail(LOONG_E_ALIGN, "loong_attn_step_fwd: q/k/v/out must be 16-byte aligned");
+  if (desc->batch == 0 || desc->q_len == 0) return LOONG_OK;
+  return desc->dtype == LOONG_BF16 ? launch_fwd_bf16(*desc, g, q, k, v, out, lse, stream)
+                                   : launch_fwd_f32(*desc, g, q, k, v, out, lse, stream);
+}
+
+int loong_attn_step_bwd(const loong_step_desc* desc, const void* q, const void* k, const void* v,
+                        const void* o, const void* d_o, const float* lse, float* delta, float* dq,
+                        float* dk, float* dv, void* stream) {
+  clear_error();
+  StepGeom g;
+  if (int rc = check_step(desc, &g)) return rc;
+  if (!q || !k || !v || !d_o || !lse || !delta || !dq || !dk || !dv)
+    return fail(LOONG_E_NULL, "loong_attn_step_bwd: NULL tensor");
+  const bool want_delta = desc->flags & LOONG_COMPUTE_DELTA;
+  if (want_delta && !o) return fail(LOONG_E_NULL, "loong_attn_step_bwd: LOONG_COMPUTE_DELTA needs o");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) ||
+      !aligned16(dk) || !aligned16(dv) || (want_delta && !aligned16(o)))
+    return fail(LOONG_E_ALIGN, "loong_attn_step_bwd: tensors must be 16-byte aligned");
+  if (desc->batch == 0) return LOONG_OK;
+  if (want_delta)
+    if (int rc = loong_bwd_delta(desc, o, d_o, delta, stream)) return rc;
+  return desc->dtype == LOONG_BF16
+             ? launch_bwd_bf16(*desc, g, q, k, v, d_o, lse, delta, dq, dk, dv, stream)
+             : launch_bwd_f32(*desc, g, q, k, v, d_o, lse, delta, dq, dk, dv, stream);
+}
+
+}  // extern "C"

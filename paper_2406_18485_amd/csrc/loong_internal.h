@@ -1,0 +1,50 @@
+// Internal declarations shared by the host side of the library (not part of the ABI).
+#pragma once
+#include <stdint.h>
+#include "loong.h"
+
+namespace loong {
+
+// Record an error text for the calling thread and hand back `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+// A run of consecutive local tokens that belong to one global chunk.
+struct Segment {
+  int32_t start;   // first local token
+  int32_t len;     // tokens
+  int32_t chunk;   // global chunk id (only compared, never used as an address)
+};
+
+// Geometry of one micro-step after validation: up to two q segments and two key
+// segments, and the class of every (q segment, key segment) block.
+struct StepGeom {
+  int32_t nq, nk;
+  Segment q[2], k[2];
+  uint8_t cls[2][2];
+};
+
+// Validate a descriptor (no device access).  Fills `g` when it succeeds.
+int check_step(const loong_step_desc* d, StepGeom* g);
+
+// 16-byte alignment test for device pointers.
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Map a hipError_t (as int) of the last launch to the ABI status.
+int check_launch(const char* what);
+
+}  // namespace loong
+
+// Kernel launchers (defined next to their kernels).  All arguments are already validated.
+namespace loong {
+int launch_fwd_f32(const loong_step_desc& d, const StepGeom& g, const void* q, const void* k,
+                   const void* v, float* out, float* lse, void* stream);
+int launch_bwd_f32(const loong_step_desc& d, const StepGeom& g, const void* q, const void* k,
+                   const void* v, const void* d_o, const float* lse, const float* delta, float* dq,
+                   float* dk, float* dv, void* stream);
+int launch_fwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, const void* k,
+                    const void* v, float* out, float* lse, void* stream);
+int launch_bwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, const void* k,
+                    const void* v, const void* d_o, const float* lse, const float* delta, float* dq,
+                    float* dk, float* dv, void* stream);
+}  // namespace loong

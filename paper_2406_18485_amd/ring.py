@@ -1,0 +1,98 @@
+"""Single-GPU replay of one device's share of Double-Ring-Attention.
+
+The ring is simulated by visiting the K/V chunks, all resident in HBM, in the order in
+which the inner and outer rings of Alg. 2 would deliver them to the simulated rank; each
+visit is one call of the library's step kernels.  torch is used for device memory and
+the stream only.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class RingShape:
+    cp: int
+    w: int
+    rank: int
+    hq: int
+    hkv: int
+    d: int
+    c: int
+    dtype: int          # B.BF16 | B.FP32
+    scale: float
+    batch: int = 1
+
+    @property
+    def L(self) -> int:
+        return 2 * self.c
+
+
+def visit_plan(shape: RingShape) -> list[dict]:
+    """Per micro-step: source rank, chunk ids and block classes, from the library."""
+    return [B.zigzag_mask(shape.cp, shape.w, shape.rank, t) for t in range(shape.cp)]
+
+
+def _desc(shape: RingShape, step: dict, flags: int) -> B.StepDesc:
+    return B.make_desc(batch=shape.batch, n_q_heads=shape.hq, n_kv_heads=shape.hkv, head_dim=shape.d,
+                       q_len=shape.L, kv_len=shape.L, dtype=shape.dtype, softmax_scale=shape.scale,
+                       causal=True, chunk_len=shape.c, q_chunk=step["q_chunk"], kv_chunk=step["kv_chunk"],
+                       flags=flags)
+
+
+class RingReplay:
+    """Buffers and launch sequence of the forward and backward replay for one rank.
+
+    k_by_src / v_by_src: [cp, batch, hkv, L, d] device tensors holding, for every source
+    rank, its zigzag chunk pair (low half first).  q, d_o: [batch, hq, L, d].
+    """
+
+    def __init__(self, shape: RingShape, device="cuda:0"):
+        self.shape = shape
+        self.dev = torch.device(device)
+        self.plan = visit_plan(shape)
+        s = shape
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        self.store_dtype = torch.bfloat16 if s.dtype == B.BF16 else torch.float32
+        self.rows = s.batch * s.hq * s.L
+        self.out = torch.empty(s.batch, s.hq, s.L, s.d, **f32)      # running fp32 output
+        self.lse = torch.empty(s.batch, s.hq, s.L, **f32)
+        self.o = torch.empty(s.batch, s.hq, s.L, s.d, dtype=self.store_dtype, device=self.dev)
+        self.delta = torch.empty(s.batch, s.hq, s.L, **f32)
+        self.dq = torch.empty(s.batch, s.hq, s.L, s.d, **f32)
+        self.dk = torch.empty(s.cp, s.batch, s.hkv, s.L, s.d, **f32)  # per source rank
+        self.dv = torch.empty(s.cp, s.batch, s.hkv, s.L, s.d, **f32)
+        self.block_out = None
+        self.block_lse = None
+
+    # ---- forward: cp x (Attention [+ Update]) then the cast to the stored activation type
+    def forward(self, q, k_by_src, v_by_src, fuse_merge=True, stream=None):
+        s = self.shape
+        B.init_running(self.rows, s.d, self.out, self.lse, stream)
+        if not fuse_merge and self.block_out is None:
+            self.block_out = torch.empty_like(self.out)
+            self.block_lse = torch.empty_like(self.lse)
+        for step in self.plan:
+            src = step["src_rank"]
+            if fuse_merge:
+                B.attn_step_fwd(_desc(s, step, B.FUSE_MERGE), q, k_by_src[src], v_by_src[src], self.out, self.lse, stream)
+            else:
+                B.attn_step_fwd(_desc(s, step, 0), q, k_by_src[src], v_by_src[src], self.block_out, self.block_lse, stream)
+                B.lse_merge(self.rows, s.d, self.out, self.lse, self.block_out, self.block_lse, stream)
+        B.finalize_out(self.rows, s.d, self.out, self.o, s.dtype, stream)
+
+    # ---- backward from the stored O and LSE: delta once, then cp step kernels
+    def backward(self, q, k_by_src, v_by_src, d_o, stream=None):
+        s = self.shape
+        self.dq.zero_()
+        first = True
+        for step in self.plan:
+            src = step["src_rank"]
+            flags = B.COMPUTE_DELTA if first else 0
+            first = False
+            B.attn_step_bwd(_desc(s, step, flags), q, k_by_src[src], v_by_src[src], self.o, d_o, self.lse,
+                            self.delta, self.dq, self.dk[src], self.dv[src], stream)

@@ -1,0 +1,289 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the fp64 oracle on the
+same seeded inputs.  Bounds: max-abs 2e-2 on O, dQ, dK, dV and 1e-3 on LSE (bf16 inputs,
+fp32 accumulation); fp32-storage cases are held to 2e-4 / 1e-4."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import paper_2406_18485_amd as P
+from gpu_harness import (DEV, TOL_LSE, TOL_O, Replayed, check_full, max_abs, oracle_full, to_dev)
+from workloads import CONFIGS, RingConfig, make_inputs, round_to_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+def _f32(*shape, seed=0, sigma=1.0):
+    return (np.random.default_rng(seed).standard_normal(shape) * sigma).astype(np.float32)
+
+
+# ------------------------------------------------------------------------------ row kernels
+@pytest.mark.parametrize("rows,d", [(1, 4), (37, 64), (1000, 128), (4099, 128), (513, 96), (65, 256), (3, 260)])
+def test_lse_merge_matches_oracle_update(rows, d):
+    out, bout = _f32(rows, d, seed=1), _f32(rows, d, seed=2)
+    lse, blse = _f32(rows, seed=3, sigma=4.0), _f32(rows, seed=4, sigma=4.0)
+    # neutral sides in every combination
+    lse[::7] = -np.inf
+    blse[::5] = -np.inf
+    out[::7] = 0.0
+    bout[::5] = 0.0
+    ref_out, ref_lse = orc.update(out, lse, bout, blse)
+    t_out, t_lse = torch.from_numpy(out).to(DEV), torch.from_numpy(lse).to(DEV)
+    P.lse_merge(rows, d, t_out, t_lse, torch.from_numpy(bout).to(DEV), torch.from_numpy(blse).to(DEV))
+    torch.cuda.synchronize()
+    got_lse = t_lse.cpu().numpy().astype(np.float64)
+    assert np.array_equal(np.isneginf(got_lse), np.isneginf(ref_lse))
+    fin = np.isfinite(ref_lse)
+    assert max_abs(got_lse[fin], ref_lse[fin]) < 2e-6 * max(1.0, np.abs(ref_lse[fin]).max(initial=0.0))
+    assert max_abs(t_out.cpu().numpy(), ref_out) < 1e-5
+    # rows that received nothing are bit-identical to what they were
+    keep = np.isneginf(blse)
+    assert np.array_equal(t_out.cpu().numpy()[keep], out[keep])
+
+
+def test_lse_merge_zero_rows_is_a_noop():
+    t = torch.zeros(4, 128, device=DEV)
+    l = torch.zeros(4, device=DEV)
+    P.lse_merge(0, 128, t, l, t, l)
+    torch.cuda.synchronize()
+
+
+def test_init_running_and_finalize():
+    rows, d = 777, 128
+    out = torch.full((rows, d), 3.0, device=DEV)
+    lse = torch.zeros(rows, device=DEV)
+    P.init_running(rows, d, out, lse)
+    torch.cuda.synchronize()
+    assert torch.all(out == 0) and torch.all(torch.isneginf(lse))
+    x = _f32(rows, d, seed=5, sigma=3.0)
+    o16 = torch.empty(rows, d, dtype=torch.bfloat16, device=DEV)
+    P.finalize_out(rows, d, torch.from_numpy(x).to(DEV), o16, P.BF16)
+    o32 = torch.empty(rows, d, dtype=torch.float32, device=DEV)
+    P.finalize_out(rows, d, torch.from_numpy(x).to(DEV), o32, P.FP32)
+    torch.cuda.synchronize()
+    assert np.array_equal(o16.float().cpu().numpy(), round_to_bf16(x))   # round to nearest even, bit exact
+    assert np.array_equal(o32.cpu().numpy(), x)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 64), ("fp32", 100)])
+def test_bwd_delta_matches_rowsum(dtype, d):
+    b, h, n = 2, 3, 301
+    o, do = _f32(b, h, n, d, seed=6), _f32(b, h, n, d, seed=7)
+    if dtype == "bf16":
+        o, do = round_to_bf16(o), round_to_bf16(do)
+    desc = P.make_desc(batch=b, n_q_heads=h, n_kv_heads=h, head_dim=d, q_len=n, kv_len=n,
+                       dtype=P.BF16 if dtype == "bf16" else P.FP32, softmax_scale=1.0)
+    delta = torch.empty(b, h, n, device=DEV)
+    P.bwd_delta(desc, to_dev(o, dtype), to_dev(do, dtype), delta)
+    torch.cuda.synchronize()
+    assert max_abs(delta.cpu().numpy(), orc.rowsum_delta(do, o)) < 2e-4
+
+
+# ------------------------------------------------------------------------------ whole replays
+def test_tiny_fp32_config_full_parity_fused_and_unfused():
+    cfg = CONFIGS[0]
+    inp = make_inputs(cfg)
+    ref = oracle_full(cfg, inp)
+    run = Replayed(cfg, inp)
+    check_full(run.run(fuse_merge=True), ref, tol_o=2e-4, tol_lse=1e-4)
+    fused_out = run.out().copy()
+    check_full(run.run(fuse_merge=False), ref, tol_o=2e-4, tol_lse=1e-4)
+    assert max_abs(fused_out, run.out()) < 1e-5
+
+
+def test_tiny_config_through_the_bf16_kernels():
+    cfg = RingConfig("tiny_bf16", cp=4, w=4, rank=0, hq=2, hkv=2, d=64, c=128, dtype="bf16", sigma=1.0, seed=1000)
+    inp = make_inputs(cfg)
+    check_full(Replayed(cfg, inp).run(), oracle_full(cfg, inp))
+
+
+SMALL = [
+    # hq hkv d   c   cp w rank
+    (2, 2, 128, 64, 2, 2, 0),
+    (2, 2, 128, 64, 2, 2, 1),
+    (4, 1, 128, 200, 4, 2, 2),    # ragged chunk, GQA 4:1, double ring
+    (8, 1, 64, 96, 2, 1, 1),      # GQA 8:1, head_dim 64
+    (6, 2, 128, 33, 3, 3, 1),     # group of 3: no head stacking
+    (2, 1, 128, 1, 2, 2, 0),      # one token per chunk
+    (4, 2, 64, 257, 2, 2, 0),
+    (1, 1, 128, 520, 2, 2, 1),    # several key tiles and a ragged tail
+]
+
+
+@pytest.mark.parametrize("hq,hkv,d,c,cp,w,rank", SMALL)
+def test_bf16_small_shapes_full_parity(hq, hkv, d, c, cp, w, rank):
+    cfg = RingConfig(f"small_h{hq}_{hkv}_d{d}_c{c}_cp{cp}_r{rank}", cp=cp, w=w, rank=rank, hq=hq, hkv=hkv, d=d, c=c,
+                     dtype="bf16", sigma=0.7, seed=77 + c)
+    inp = make_inputs(cfg)
+    ref = oracle_full(cfg, inp)
+    run = Replayed(cfg, inp)
+    check_full(run.run(fuse_merge=True), ref)
+    check_full(run.run(fuse_merge=False), ref)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+@pytest.mark.parametrize("which_rank", ["first", "middle"])
+def test_shrunken_benchmark_configs_full_parity(idx, which_rank):
+    cfg = CONFIGS[idx].shrunk(320)
+    if which_rank == "middle":
+        cfg = cfg.on_rank(cfg.cp // 2)
+    if cfg.cp >= 16:
+        cfg = cfg.shrunk(192)
+    inp = make_inputs(cfg)
+    check_full(Replayed(cfg, inp).run(), oracle_full(cfg, inp))
+
+
+def test_forward_is_bit_reproducible_and_order_of_visits_does_not_matter():
+    cfg = CONFIGS[3].shrunk(256)                     # cp=16, inner ring 4
+    inp = make_inputs(cfg)
+    a = Replayed(cfg, inp).run(backward=True)
+    out1, lse1 = a.out().copy(), a.lse().copy()
+    a.run(backward=False)
+    assert np.array_equal(out1, a.out()) and np.array_equal(lse1, a.lse())
+    lin = Replayed(RingConfig(**{**cfg.__dict__, "w": cfg.cp}), inp).run()
+    assert [s["src_rank"] for s in lin.rep.plan] != [s["src_rank"] for s in a.rep.plan]
+    assert max_abs(lin.out(), out1) < 1e-5 and max_abs(lin.lse(), lse1) < 1e-5
+    dk_a, dv_a = a.dkv_global()
+    dk_l, dv_l = lin.dkv_global()
+    assert max_abs(dk_a, dk_l) < 1e-4 and max_abs(dv_a, dv_l) < 1e-4 and max_abs(a.dq(), lin.dq()) < 1e-4
+
+
+# ------------------------------------------------------------------------------ direct calls, edge cases
+def _direct(dtype, b, hq, hkv, d, nq, nk, seed, strided=False, accum=False):
+    rng = np.random.default_rng(seed)
+    mk = (lambda *s: round_to_bf16(rng.standard_normal(s).astype(np.float32) * 0.8)) if dtype == "bf16" else \
+         (lambda *s: rng.standard_normal(s).astype(np.float32))
+    q, do = mk(b, hq, nq, d), mk(b, hq, nq, d)
+    k_buf, v_buf = mk(b, hkv, max(nk, 1), d), mk(b, hkv, max(nk, 1), d)   # never an empty allocation
+    k, v = k_buf[:, :, :nk], v_buf[:, :, :nk]
+    scale = 1.0 / np.sqrt(d)
+    code = P.BF16 if dtype == "bf16" else P.FP32
+    kw = {}
+    if strided:   # token-major storage [b, token, head, d] viewed as [b, head, token, d]
+        kw = dict(q_stride=(nq * hq * d, d, hq * d), kv_stride=(nk * hkv * d, d, hkv * d), o_stride=(nq * hq * d, d, hq * d))
+    desc = P.make_desc(batch=b, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, q_len=nq, kv_len=nk, dtype=code,
+                       softmax_scale=scale, **kw)
+
+    def up(x, dt):
+        t = to_dev(x, dt)
+        return t.permute(0, 2, 1, 3).contiguous() if strided else t   # physical layout
+
+    tq, tdo = up(q, dtype), up(do, dtype)
+    tk, tv = (up(k, dtype), up(v, dtype)) if nk else (up(k_buf, dtype), up(v_buf, dtype))
+    phys = (b, nq, hq, d) if strided else (b, hq, nq, d)
+    out = torch.full(phys, 7.0, device=DEV)
+    lse = torch.full((b, hq, nq), 7.0, device=DEV)
+    P.attn_step_fwd(desc, tq, tk, tv, out, lse)
+    torch.cuda.synchronize()
+    got_out = (out.permute(0, 2, 1, 3) if strided else out).cpu().numpy()
+    got_lse = lse.cpu().numpy()
+    refs = [orc.attention_backward(q[i], k[i], v[i], do[i], np.zeros(nq, int), np.zeros(nk, int), scale, causal=False)
+            for i in range(b)]
+    ref_out = np.stack([r[3] for r in refs])
+    ref_lse = np.stack([r[4] for r in refs])
+    tol_o, tol_l = (TOL_O, TOL_LSE) if dtype == "bf16" else (2e-4, 1e-4)
+    if nk == 0:
+        assert np.all(got_out == 0) and np.all(np.isneginf(got_lse))
+    else:
+        assert max_abs(got_out, ref_out) <= tol_o and max_abs(got_lse, ref_lse) <= tol_l
+    # backward from the oracle's exact row statistics
+    o_store = up(ref_out.astype(np.float32), "fp32").to(torch.bfloat16 if dtype == "bf16" else torch.float32)
+    lse_dev = torch.from_numpy(np.where(np.isfinite(ref_lse), ref_lse, -np.inf).astype(np.float32)).to(DEV)
+    delta = torch.empty(b, hq, nq, device=DEV)
+    dq = torch.zeros(phys, device=DEV)
+    fill = 0.5 if accum else 9.0
+    dk = torch.full((b, hkv, max(nk, 1), d), fill, device=DEV)[:, :, :nk]
+    dv = torch.full((b, hkv, max(nk, 1), d), fill, device=DEV)[:, :, :nk]
+    assert nk == 0 or (dk.is_contiguous() and dv.is_contiguous())
+    desc.flags = P.COMPUTE_DELTA | (P.ACCUM_DKV if accum else 0)
+    P.attn_step_bwd(desc, tq, tk, tv, o_store, tdo, lse_dev, delta, dq, dk, dv)
+    torch.cuda.synchronize()
+    if nk > 0 and nq > 0:
+        off = fill if accum else 0.0
+        assert max_abs((dq.permute(0, 2, 1, 3) if strided else dq).cpu().numpy(), np.stack([r[0] for r in refs])) <= tol_o
+        assert max_abs(dk.cpu().numpy() - off, np.stack([r[1] for r in refs])) <= tol_o
+        assert max_abs(dv.cpu().numpy() - off, np.stack([r[2] for r in refs])) <= tol_o
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("nq,nk", [(333, 517), (1, 1), (64, 0), (70, 3), (5, 700)])
+def test_non_causal_ragged_lengths(dtype, nq, nk):
+    _direct(dtype, 2, 4, 2, 128 if dtype == "bf16" else 32, nq, nk, seed=nq + nk)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_token_major_strides_and_accumulating_dkv(dtype):
+    _direct(dtype, 2, 4, 2, 64, 130, 190, seed=3, strided=True, accum=True)
+
+
+def test_q_len_zero_is_a_noop():
+    desc = P.make_desc(batch=1, n_q_heads=2, n_kv_heads=2, head_dim=128, q_len=0, kv_len=64, dtype=P.BF16, softmax_scale=0.1)
+    x = torch.zeros(1, 2, 64, 128, dtype=torch.bfloat16, device=DEV)
+    f = torch.zeros(1, 2, 64, 128, device=DEV)
+    P.attn_step_fwd(desc, x, x, x, f, f)
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------ full benchmark sizes
+def test_config2_full_size_full_tensor_parity():
+    cfg = CONFIGS[1]
+    inp = make_inputs(cfg)
+    run = Replayed(cfg, inp).run()
+    check_full(run, oracle_full(cfg, inp))
+
+
+def _sample_rows(cfg, n_random, seed):
+    c, L = cfg.c, cfg.L
+    edge = {0, 1, c - 1, c, c + 1, L - 1, L - 2}
+    for t in (16, 32, 64, 128, 256):
+        for base in (0, c):
+            for k in (1, 3):
+                edge.update({base + k * t - 1, base + k * t, base + k * t + 1})
+    edge = {r for r in edge if 0 <= r < L}
+    rng = np.random.default_rng(seed)
+    rows = sorted(edge | set(rng.integers(0, L, n_random).tolist()))
+    return np.array(rows, dtype=np.int64)
+
+
+@pytest.mark.parametrize("idx,n_random", [(2, 24), (3, 16), (4, 8)])
+def test_full_size_sampled_rows_and_gradient_identities(idx, n_random):
+    cfg = CONFIGS[idx]
+    inp = make_inputs(cfg)
+    run = Replayed(cfg, inp).run()
+    rows = _sample_rows(cfg, n_random, seed=idx)
+    pos_q = orc.zigzag_positions(cfg.cp, cfg.rank, cfg.c)[rows]
+    # exact rows: O, LSE and dQ of the sampled rows over all S keys
+    errs = {"out": 0.0, "lse": 0.0, "dq": 0.0}
+    got_out, got_lse, got_dq = run.out(), run.lse(), run.dq()
+    g = cfg.hq // cfg.hkv
+    for h in range(cfg.hq):
+        sl = slice(h // g, h // g + 1)
+        dq, _, _, out, lse, _ = orc.attention_backward(inp["q"][h:h + 1, rows], inp["k_all"][sl], inp["v_all"][sl],
+                                                       inp["d_out"][h:h + 1, rows], pos_q, np.arange(cfg.S), cfg.scale)
+        errs["out"] = max(errs["out"], max_abs(got_out[h, rows], out[0]))
+        errs["lse"] = max(errs["lse"], max_abs(got_lse[h, rows], lse[0]))
+        errs["dq"] = max(errs["dq"], max_abs(got_dq[h, rows], dq[0]))
+    print(f"[sampled] {cfg.name}: {errs} rows={len(rows)}", flush=True)
+    assert errs["out"] <= TOL_O and errs["dq"] <= TOL_O and errs["lse"] <= TOL_LSE
+    # identities that hold at any size, on the device results
+    dk = run.rep.dk.double().sum(dim=(0, 1, 3)).cpu().numpy()          # [hkv, d]: sum over all keys
+    dv = run.rep.dv.double().sum(dim=(0, 1, 3)).cpu().numpy()
+    dk_mass = run.rep.dk.double().abs().sum(dim=(0, 1, 3)).cpu().numpy()
+    dv_mass = run.rep.dv.double().abs().sum(dim=(0, 1, 3)).cpu().numpy()
+    do_sum = inp["d_out"].astype(np.float64).reshape(cfg.hkv, g, cfg.L, cfg.d).sum(axis=(1, 2))
+    r_dk = np.abs(dk).max() / dk_mass.max()
+    r_dv = np.abs(dv - do_sum).max() / dv_mass.max()
+    qdq = float((run.rep.dq[0].double().cpu().numpy() * inp["q"]).sum())
+    kdk = 0.0
+    for s in range(cfg.cp):
+        pos = orc.zigzag_positions(cfg.cp, s, cfg.c)
+        kdk += float((run.rep.dk[s, 0].double().cpu().numpy() * inp["k_all"][:, pos]).sum())
+    scale_qk = float(np.abs(run.rep.dq[0].double().cpu().numpy() * inp["q"]).sum())
+    r_qk = abs(qdq - kdk) / scale_qk
+    print(f"[identities] {cfg.name}: sum dK {r_dk:.2e}  sum dV {r_dv:.2e}  <q,dQ>-<k,dK> {r_qk:.2e}", flush=True)
+    assert r_dk < 2e-3 and r_dv < 2e-3 and r_qk < 2e-3
+    if idx == 3:   # double ring vs plain ring: same result up to fp32 rounding
+        lin = Replayed(RingConfig(**{**cfg.__dict__, "w": cfg.cp}), inp).run()
+        assert max_abs(lin.out(), got_out) < 1e-5 and max_abs(lin.lse(), got_lse) < 1e-5
+        assert float((lin.rep.dk - run.rep.dk).abs().max()) < 1e-3
+        assert float((lin.rep.dv - run.rep.dv).abs().max()) < 1e-3
