@@ -2,18 +2,32 @@
 // chunk against one visiting K/V chunk, with the Update optionally folded in by starting
 // the online softmax from the running (out, lse).
 //
-// Work split.  A workgroup of NW waves owns 32*NW query rows: GS query heads that share
-// one kv head (GS | group size) times 32*NW/GS consecutive rows of one zigzag half, so a
-// K/V tile staged in LDS serves every head of the group.  Each wave owns 32 rows.
-// Per tile of BN keys a wave computes S^T = K Q^T (keys x rows) so that every lane holds
-// one query row (two lanes per row, 16 keys each per 32-key block): the row maximum and
-// sum are in-lane reductions plus one exchange with the lane 32 places away, and the
-// accumulator layout of P^T is already the B-operand layout of the second product
-// O^T += V^T P^T, given that V^T is read from LDS with the same key order.
-// V is stored in LDS as pairs of keys interleaved per column so that this read is four
-// 32-bit loads.  Blocks of the (q half, k half) grid that are invisible are never
-// visited; only tiles that touch the diagonal or a ragged end apply a mask.
+// Shape of the computation.  A workgroup has eight waves (two per SIMD) = NRB row blocks
+// x KS key splits.  Every wave owns 32 query rows of one head and keeps their Q fragments
+// and fp32 O^T accumulators in registers.  Per iteration a tile of KS*BNS keys is staged
+// in LDS and the wave takes its BNS keys: S^T = K Q^T (keys x rows) with
+// v_mfma_f32_32x32x16_bf16, so a lane holds one query row (row maximum and sum are in-lane
+// reductions plus one exchange with the lane 32 places away) and the accumulator layout of
+// P^T already is the B operand of O^T += V^T P^T.
+//
+// Staging.  K and V tiles go from global memory straight into LDS (global_load_lds, 16 B
+// per lane, no registers, no LDS writes by the waves), row-major as in memory, NBUF tiles
+// deep.  Each wave-level load fills 1 KB of LDS contiguously, so the rows cannot be padded;
+// bank conflicts are avoided by permuting which 16-byte piece of a row each lane fetches
+// (an XOR of the piece index with low bits of the row).  K operands are then single
+// 16-byte LDS reads; V^T operands are two transposing reads (ds_read_b64_tr_b16), each
+// giving a lane four consecutive keys of one column: exactly the two runs of four keys a
+// lane holds per 16-key slice of the P^T accumulator.
+//
+// Work split.  With KS = 1 eight waves (256 rows, or GS heads of one kv group x 256/GS
+// rows) share each staged tile.  When a step has too few rows to fill the chip, KS = 2 or
+// 4 waves share the same rows and split every tile's keys, each with its own online
+// softmax; the partial results are combined through LDS at the end (the log-sum-exp
+// algebra of Update).  Blocks of the (q half, k half) grid that are invisible are never
+// visited; only tiles touching the diagonal or a ragged end apply a mask.
 #include <hip/hip_runtime.h>
+
+#include <cstdlib>
 
 #include "device_utils.h"
 #include "loong_internal.h"
@@ -22,6 +36,11 @@ namespace loong {
 namespace {
 
 constexpr float kRescaleSlack = 8.f;  // the running maximum may lag the true one by 2^8
+constexpr int kFwdWaves = 8;
+
+typedef short v4i16_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i16_t lds_v4i16_t;
+typedef __attribute__((address_space(3))) void lds_void_t;
 
 struct FwdParams {
   const uint16_t *q, *k, *v;
@@ -38,26 +57,40 @@ struct FwdParams {
   int total_wg;
 };
 
-template <int D, int NW, int BN>
+template <int D, int KS>
 struct FwdCfg {
-  static constexpr int NT = NW * 64;
-  static constexpr int KSTR = D + 8;    // bf16 per K row in LDS (pad: 16-lane b128 reads hit all banks once)
-  static constexpr int VSTR = D + 16;   // dwords per key-pair row of V in LDS
-  static constexpr int CPR = D / 8;     // 16-byte pieces per row
-  static constexpr int K_UNITS = BN * CPR;
-  static constexpr int V_UNITS = (BN / 2) * CPR;
-  static constexpr int K_PT = (K_UNITS + NT - 1) / NT;
-  static constexpr int V_PT = (V_UNITS + NT - 1) / NT;
+  static constexpr int NT = kFwdWaves * 64;
+  static constexpr int NRB = kFwdWaves / KS;       // 32-row blocks per workgroup
+  static constexpr int BNS = KS == 1 ? 64 : 32;    // keys per wave and iteration
+  static constexpr int TK = KS * BNS;              // keys staged per iteration
+  static constexpr int ROWB = D * 2;               // bytes per K or V row
+  static constexpr int CH = D / 8;                 // 16-byte pieces per row
+  static constexpr int RP = 256 / ROWB;            // rows per 256 bytes (one sweep over all LDS banks)
+  static constexpr int TILE_B = TK * ROWB;         // bytes of one K (or V) tile
+  static constexpr int BUF_B = 2 * TILE_B;
+  static constexpr int NBUF = BUF_B * 4 <= 131072 ? 4 : 2;
+  static constexpr int PD = NBUF - 1;              // tiles in flight ahead of the one being used
+  static constexpr int RPI = 1024 / ROWB;          // rows filled by one wave-level load
+  static constexpr int KI = TILE_B / 1024 / kFwdWaves;  // loads per wave per K (or V) tile
+  static constexpr int SLOT_F4 = (D / 32) * 4 + 1; // float4 per lane of one wave's partial result
+  static constexpr int TILE_BYTES = NBUF * BUF_B;
+  static constexpr int COMB_BYTES = (KS - 1) * NRB * SLOT_F4 * 64 * 16;
+  static constexpr int SMEM_BYTES = TILE_BYTES > COMB_BYTES ? TILE_BYTES : COMB_BYTES;
+  static_assert(KI >= 1 && KI * 1024 * kFwdWaves == TILE_B, "tile must split evenly over the waves");
 };
 
-template <int D, int NW, int BN>
-__global__ __launch_bounds__(NW * 64) void fwd_kernel(const FwdParams p) {
-  using C = FwdCfg<D, NW, BN>;
-  constexpr int NJB = BN / 32;  // 32-key blocks per tile
-  constexpr int NDB = D / 32;   // 32-column blocks of the output
-  constexpr int NKS = D / 16;   // contraction slices of Q K^T
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[2][BN * C::KSTR];
-  __shared__ __attribute__((aligned(16))) uint32_t Vs[2][(BN / 2) * C::VSTR];
+// s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <int D, int KS>
+__global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) {
+  using C = FwdCfg<D, KS>;
+  constexpr int NRB = C::NRB, BNS = C::BNS, TK = C::TK, NBUF = C::NBUF, PD = C::PD, KI = C::KI;
+  constexpr int NJB = BNS / 32, NDB = D / 32, NKS = D / 16, ROWB = C::ROWB, CH = C::CH, RP = C::RP;
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[C::SMEM_BYTES];
 
   // ---- which (batch, head group, q tile): consecutive logical ids sit on one XCD, and
   // within a head group the tiles with the most visible keys come first
@@ -69,34 +102,37 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(const FwdParams p) {
   const int b = bh / p.hgroups, hg = bh - b * p.hgroups;
   const int qa = tt >= p.ntile[0] ? 1 : 0;
   const int tile = qa ? tt - p.ntile[0] : tt;
-  const int BMH = 32 * NW / p.GS;
+  const int BMH = 32 * NRB / p.GS;
   const int row0_wg = tile * BMH;
-  const Segment qseg = p.g.q[qa];
+  const Segment qseg = qa ? p.g.q[1] : p.g.q[0];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hh = lane >> 5;
-  const int gq = wave % p.GS, rb = wave / p.GS;
+  const int rb = wave % NRB, ksp = wave / NRB;  // row block, key split
+  const int gq = rb % p.GS, rslot = rb / p.GS;
   const int h = hg * p.GS + gq, hk = h / p.G;
-  const int wrow0 = row0_wg + rb * 32;
+  const int wrow0 = row0_wg + rslot * 32;
   const int my_off = wrow0 + l32;
   const bool wave_live = wrow0 < qseg.len;
   const bool row_ok = my_off < qseg.len;
   const int my_row = qseg.start + min(my_off, qseg.len - 1);
   const int last_off_wg = min(row0_wg + BMH, qseg.len) - 1;
 
-  // ---- visible key tiles of this workgroup
-  int kend[2] = {0, 0}, ntk[2] = {0, 0};
-  for (int kb = 0; kb < p.g.nk; ++kb) {
-    const int cls = p.g.cls[qa][kb];
-    kend[kb] = cls == LOONG_SKIP ? 0 : cls == LOONG_FULL ? p.g.k[kb].len : min(p.g.k[kb].len, last_off_wg + 1);
-    ntk[kb] = (kend[kb] + BN - 1) / BN;
-  }
-  const int total_t = ntk[0] + ntk[1];
+  // ---- visible key tiles of this workgroup (per-segment facts kept in scalars: nothing in
+  // the main loop indexes the kernel arguments dynamically)
+  const int cls0 = qa ? p.g.cls[1][0] : p.g.cls[0][0];
+  const int cls1 = p.g.nk > 1 ? (qa ? p.g.cls[1][1] : p.g.cls[0][1]) : LOONG_SKIP;
+  const int klen0 = p.g.k[0].len, klen1 = p.g.nk > 1 ? p.g.k[1].len : 0;
+  const int kstart0 = p.g.k[0].start, kstart1 = p.g.nk > 1 ? p.g.k[1].start : 0;
+  const int kend0 = cls0 == LOONG_SKIP ? 0 : cls0 == LOONG_FULL ? klen0 : min(klen0, last_off_wg + 1);
+  const int kend1 = cls1 == LOONG_SKIP ? 0 : cls1 == LOONG_FULL ? klen1 : min(klen1, last_off_wg + 1);
+  const int ntk0 = (kend0 + TK - 1) / TK, ntk1 = (kend1 + TK - 1) / TK;
+  const int total_t = ntk0 + ntk1;
 
   float* out_row = p.out + b * p.os[0] + h * p.os[1] + (int64_t)my_row * p.os[2];
   float* lse_ptr = p.lse + ((int64_t)b * p.Hq + h) * p.q_len + my_row;
 
   if (total_t == 0) {  // nothing visible: neutral partial result, or leave the running one
-    if (!p.fuse && row_ok) {
+    if (!p.fuse && ksp == 0 && row_ok) {
 #pragma unroll
       for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -115,14 +151,15 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(const FwdParams p) {
     for (int ks = 0; ks < NKS; ++ks) qf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(qrow + ks * 16 + hh * 8));
   }
 
-  // ---- running state: maximum (log2 units), partial row sum of this half, O^T accumulators
+  // ---- running state: maximum (log2 units), partial row sum of this half, O^T accumulators.
+  // Only split 0 starts from the running result.
   float m_run = -INFINITY, l_run = 0.f;
   floatx16_t o[NDB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
     for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-  if (p.fuse) {
+  if (p.fuse && ksp == 0) {
     const float prev = *lse_ptr;
     if (prev != -INFINITY) {
       m_run = prev * kLog2e;
@@ -137,155 +174,197 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(const FwdParams p) {
     }
   }
 
-  // ---- global -> register staging of one K/V tile, and register -> LDS
-  uint4 kreg[C::K_PT], vreg[C::V_PT][2];
-  const uint16_t* kbase = p.k + b * p.ks[0] + hk * p.ks[1];
-  const uint16_t* vbase = p.v + b * p.ks[0] + hk * p.ks[1];
+  // ---- staging: global -> LDS directly.  Load i of this wave fills LDS bytes
+  // [(wave + 8 i) * 1024, +1024) of the K (or V) tile: row (wave + 8 i) * RPI + lane / CH,
+  // piece position lane % CH, which holds piece (position ^ swizzle(row)) of that row.
+  const unsigned char* kbase = reinterpret_cast<const unsigned char*>(p.k + b * p.ks[0] + hk * p.ks[1]);
+  const unsigned char* vbase = reinterpret_cast<const unsigned char*>(p.v + b * p.ks[0] + hk * p.ks[1]);
+  const int64_t rowbytes = p.ks[2] * 2;
+  const int ld_row = wave * C::RPI + lane / CH;  // row inside the tile for i = 0; later loads add 8*RPI rows
+  const int ld_pos = lane % CH;
+  const uint32_t k_piece = (uint32_t)(ld_pos ^ ((ld_row / RP) & (CH - 1))) * 16;
+  const uint32_t v_piece = (uint32_t)(ld_pos ^ (((ld_row / RP) & (4 / RP - 1)) * 2)) * 16;
   auto tile_of = [&](int t, int& kb, int& j0) {
-    kb = t < ntk[0] ? 0 : 1;
-    j0 = (t - (kb ? ntk[0] : 0)) * BN;
+    kb = t < ntk0 ? 0 : 1;
+    j0 = (t - (kb ? ntk0 : 0)) * TK;
   };
-  auto issue_loads = [&](int t) {
+  auto issue_tile = [&](int t) {
     int kb, j0;
     tile_of(t, kb, j0);
-    const int len = p.g.k[kb].len, start = p.g.k[kb].start;
+    const int len = kb ? klen1 : klen0, start = kb ? kstart1 : kstart0;
+    const int64_t tb = (int64_t)(start + j0) * rowbytes;
+    const int last = len - 1 - j0;  // last valid row of the tile (>= 0); later rows repeat it
+    unsigned char* kl = smem + (t % NBUF) * C::BUF_B + wave * 1024;
+    unsigned char* vl = kl + C::TILE_B;
 #pragma unroll
-    for (int n = 0; n < C::K_PT; ++n) {
-      const int u = tid + n * C::NT;
-      if (C::K_UNITS % C::NT == 0 || u < C::K_UNITS) {
-        const int r = u / C::CPR, cc = u - r * C::CPR;
-        const int64_t row = start + min(j0 + r, len - 1);
-        kreg[n] = *reinterpret_cast<const uint4*>(kbase + row * p.ks[2] + cc * 8);
-      }
-    }
-#pragma unroll
-    for (int n = 0; n < C::V_PT; ++n) {
-      const int u = tid + n * C::NT;
-      if (C::V_UNITS % C::NT == 0 || u < C::V_UNITS) {
-        const int kp = u / C::CPR, cc = u - kp * C::CPR;
-        const int64_t r0 = start + min(j0 + 2 * kp, len - 1), r1 = start + min(j0 + 2 * kp + 1, len - 1);
-        vreg[n][0] = *reinterpret_cast<const uint4*>(vbase + r0 * p.ks[2] + cc * 8);
-        vreg[n][1] = *reinterpret_cast<const uint4*>(vbase + r1 * p.ks[2] + cc * 8);
-      }
-    }
-  };
-  auto store_lds = [&](int buf) {
-#pragma unroll
-    for (int n = 0; n < C::K_PT; ++n) {
-      const int u = tid + n * C::NT;
-      if (C::K_UNITS % C::NT == 0 || u < C::K_UNITS) {
-        const int r = u / C::CPR, cc = u - r * C::CPR;
-        *reinterpret_cast<uint4*>(&Ks[buf][r * C::KSTR + cc * 8]) = kreg[n];
-      }
-    }
-#pragma unroll
-    for (int n = 0; n < C::V_PT; ++n) {
-      const int u = tid + n * C::NT;
-      if (C::V_UNITS % C::NT == 0 || u < C::V_UNITS) {
-        const int kp = u / C::CPR, cc = u - kp * C::CPR;
-        const uint4 a = vreg[n][0], bb = vreg[n][1];  // keys 2kp and 2kp+1, columns 8cc..8cc+7
-        uint4 w0, w1;  // dword c = (key 2kp, key 2kp+1) of column 8cc + c
-        w0.x = (a.x & 0xffffu) | (bb.x << 16); w0.y = (a.x >> 16) | (bb.x & 0xffff0000u);
-        w0.z = (a.y & 0xffffu) | (bb.y << 16); w0.w = (a.y >> 16) | (bb.y & 0xffff0000u);
-        w1.x = (a.z & 0xffffu) | (bb.z << 16); w1.y = (a.z >> 16) | (bb.z & 0xffff0000u);
-        w1.z = (a.w & 0xffffu) | (bb.w << 16); w1.w = (a.w >> 16) | (bb.w & 0xffff0000u);
-        uint32_t* dst = &Vs[buf][kp * C::VSTR + cc * 8];
-        *reinterpret_cast<uint4*>(dst) = w0;
-        *reinterpret_cast<uint4*>(dst + 4) = w1;
-      }
+    for (int i = 0; i < KI; ++i) {
+      const int r = min(ld_row + i * 8 * C::RPI, last);
+      const int64_t ro = tb + (int64_t)r * rowbytes;
+      __builtin_amdgcn_global_load_lds(kbase + ro + k_piece, (lds_void_t*)(kl + i * 8192), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(vbase + ro + v_piece, (lds_void_t*)(vl + i * 8192), 16, 0, 0);
     }
   };
 
-  issue_loads(0);
-  store_lds(0);
-  __syncthreads();
+  // ---- LDS read offsets of this lane (bytes inside a tile; the wave's split and the block
+  // and slice indices are added as constants)
+  // K operand: row l32 (+32 jb), pieces 2 ks + hh
+  uint32_t k_rd[NKS];
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) k_rd[ks] = l32 * ROWB + ((2 * ks + hh) ^ ((l32 / RP) & (CH - 1))) * 16;
+  // V^T operand via transposing reads: in a group of 16 lanes, lane i points at row i / 4
+  // of a run of four keys and at columns 4 (i % 4) .. +3 of a 16-column strip; it receives
+  // the four keys of column i of the strip.  Lanes 0-31 / 32-63 take runs 4 hh .. 4 hh + 3.
+  uint32_t v_rd[NDB];
+  {
+    const int i16 = lane & 15, r = i16 >> 2, qd = i16 & 3, strip = (lane >> 4) & 1;
+    const int sw = ((r / RP) & (4 / RP - 1)) * 2;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      const int piece = db * 4 + strip * 2 + (qd >> 1);
+      v_rd[db] = (4 * hh + r) * ROWB + (piece ^ sw) * 16 + (qd & 1) * 8;
+    }
+  }
+
+  // ---- per-tile pieces.  A wave skips a tile whose keys (its share of the staged tile) lie
+  // past the end of the segment or past all of its rows.
+  auto my_keys = [&](int t, int& j0, int& klen, bool& isdiag) {
+    int kb;
+    tile_of(t, kb, j0);
+    j0 += ksp * BNS;
+    klen = kb ? klen1 : klen0;
+    isdiag = (kb ? cls1 : cls0) == LOONG_DIAG;
+    return wave_live && j0 < klen && !(isdiag && j0 > wrow0 + 31);
+  };
+
+  // ---- pipeline: PD tiles in flight
+#pragma unroll
+  for (int t = 0; t < PD; ++t)
+    if (t < total_t) issue_tile(t);
 
   for (int t = 0; t < total_t; ++t) {
-    const int cur = t & 1;
-    if (t + 1 < total_t) issue_loads(t + 1);
-    int kb, j0;
-    tile_of(t, kb, j0);
-    const int klen = p.g.k[kb].len;
-    const bool isdiag = p.g.cls[qa][kb] == LOONG_DIAG;
-    // a wave whose rows all lie before this tile's first key has nothing to do here
-    if (wave_live && !(isdiag && j0 > wrow0 + 31)) {
-      // ---- S^T = K Q^T
-      floatx16_t s[NJB];
+    // this wave's loads of tile t have landed when at most the later tiles' are outstanding
+    const int later = min(PD - 1, total_t - 1 - t);
+    if (later >= 2) wait_vmcnt<2 * 2 * KI>();
+    else if (later == 1) wait_vmcnt<2 * KI>();
+    else wait_vmcnt<0>();
+    __syncthreads();  // every wave's part of tile t is in LDS; everyone has finished tile t-1
+    if (t + PD < total_t) issue_tile(t + PD);  // into the buffer tile t-1 used
+
+    int j0, klen;
+    bool isdiag;
+    if (!my_keys(t, j0, klen, isdiag)) continue;
+    const unsigned char* Kt = smem + (t % NBUF) * C::BUF_B + ksp * BNS * ROWB;
+    const unsigned char* Vt = smem + (t % NBUF) * C::BUF_B + C::TILE_B + ksp * BNS * ROWB;
+
+    // ---- S^T = K Q^T
+    floatx16_t s[NJB];
 #pragma unroll
-      for (int jb = 0; jb < NJB; ++jb)
+    for (int jb = 0; jb < NJB; ++jb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[jb][v] = 0.f;
+      for (int v = 0; v < 16; ++v) s[jb][v] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks)
-#pragma unroll
-        for (int jb = 0; jb < NJB; ++jb) {
-          const uint4 a = *reinterpret_cast<const uint4*>(&Ks[cur][(jb * 32 + l32) * C::KSTR + ks * 16 + hh * 8]);
-          s[jb] = mfma32(as_bf16x8(a), qf[ks], s[jb]);
-        }
-      // ---- mask (diagonal or ragged end only)
-      if (j0 + BN > klen || (isdiag && j0 + BN - 1 > wrow0)) {
-#pragma unroll
-        for (int jb = 0; jb < NJB; ++jb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int key = j0 + jb * 32 + acc_row(v, hh);
-            const bool ok = key < klen && (!isdiag || key <= my_off);
-            s[jb][v] = ok ? s[jb][v] : -INFINITY;
-          }
-      }
-      // ---- online softmax with a lagging maximum
-      float mx = s[0][0];
-#pragma unroll
-      for (int jb = 0; jb < NJB; ++jb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[jb][v]);
-      mx = fmaxf(mx, other_half(mx));
-      const float m_cand = mx * p.c;
-      if (__builtin_amdgcn_ballot_w64(m_cand > m_run + kRescaleSlack) != 0) {
-        const float m_new = fmaxf(m_run, m_cand);
-        const float alpha = m_new == -INFINITY ? 1.f : fast_exp2(m_run - m_new);
-        l_run *= alpha;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
-        m_run = m_new;
-      }
-      const float m_use = m_run == -INFINITY ? 0.f : m_run;
-      uint4 pk[NJB][2];
+    for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
       for (int jb = 0; jb < NJB; ++jb) {
-        float e[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          e[v] = fast_exp2(fmaf(s[jb][v], p.c, -m_use));
-          l_run += e[v];
-        }
-#pragma unroll
-        for (int sl = 0; sl < 2; ++sl)
-          pk[jb][sl] = make_uint4(pack_bf16x2(e[8 * sl + 0], e[8 * sl + 1]), pack_bf16x2(e[8 * sl + 2], e[8 * sl + 3]),
-                                  pack_bf16x2(e[8 * sl + 4], e[8 * sl + 5]), pack_bf16x2(e[8 * sl + 6], e[8 * sl + 7]));
+        const uint4 a = *reinterpret_cast<const uint4*>(Kt + jb * 32 * ROWB + k_rd[ks]);
+        s[jb] = mfma32(as_bf16x8(a), qf[ks], s[jb]);
       }
-      // ---- O^T += V^T P^T.  Element e of the B operand is key 16*sl + 8*(e/4) + 4*hh + e%4
-      // of block jb, so the A operand takes key pairs 8*sl + {2hh, 2hh+1, 2hh+4, 2hh+5}.
+    // ---- mask (diagonal or ragged end only)
+    if (j0 + BNS > klen || (isdiag && j0 + BNS - 1 > wrow0)) {
 #pragma unroll
       for (int jb = 0; jb < NJB; ++jb)
 #pragma unroll
-        for (int sl = 0; sl < 2; ++sl) {
-          const uint32_t* vp = &Vs[cur][(jb * 16 + sl * 8 + 2 * hh) * C::VSTR + l32];
-#pragma unroll
-          for (int db = 0; db < NDB; ++db) {
-            uint4 a;
-            a.x = vp[db * 32];
-            a.y = vp[C::VSTR + db * 32];
-            a.z = vp[4 * C::VSTR + db * 32];
-            a.w = vp[5 * C::VSTR + db * 32];
-            o[db] = mfma32(as_bf16x8(a), as_bf16x8(pk[jb][sl]), o[db]);
-          }
+        for (int v = 0; v < 16; ++v) {
+          const int key = j0 + jb * 32 + acc_row(v, hh);
+          const bool ok = key < klen && (!isdiag || key <= my_off);
+          s[jb][v] = ok ? s[jb][v] : -INFINITY;
         }
     }
-    if (t + 1 < total_t) store_lds(cur ^ 1);
+    // ---- online softmax with a lagging maximum
+    float mx = s[0][0];
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[jb][v]);
+    mx = fmaxf(mx, other_half(mx));
+    const float m_cand = mx * p.c;
+    if (__builtin_amdgcn_ballot_w64(m_cand > m_run + kRescaleSlack) != 0) {
+      const float m_new = fmaxf(m_run, m_cand);
+      const float alpha = m_new == -INFINITY ? 1.f : fast_exp2(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+      m_run = m_new;
+    }
+    const float m_use = m_run == -INFINITY ? 0.f : m_run;
+    uint4 pk[NJB][2];
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) {
+      float e[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        e[v] = fast_exp2(fmaf(s[jb][v], p.c, -m_use));
+        l_run += e[v];
+      }
+#pragma unroll
+      for (int sl = 0; sl < 2; ++sl)
+        pk[jb][sl] = make_uint4(pack_bf16x2(e[8 * sl + 0], e[8 * sl + 1]), pack_bf16x2(e[8 * sl + 2], e[8 * sl + 3]),
+                                pack_bf16x2(e[8 * sl + 4], e[8 * sl + 5]), pack_bf16x2(e[8 * sl + 6], e[8 * sl + 7]));
+    }
+    // ---- O^T += V^T P^T.  Element e of the B operand is key 16 sl + 8 (e / 4) + 4 hh + e % 4
+    // of block jb: the A operand is the run starting at key 16 sl + 4 hh and the run 8 keys on.
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb)
+#pragma unroll
+      for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          const unsigned char* vp = Vt + (jb * 32 + sl * 16) * ROWB + v_rd[db];
+          const v4i16_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t*)vp);
+          const v4i16_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t*)(vp + 8 * ROWB));
+          typedef short v8i16_t __attribute__((ext_vector_type(8)));
+          const v8i16_t a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o[db] = mfma32(__builtin_bit_cast(bf16x8_t, a), as_bf16x8(pk[jb][sl]), o[db]);
+        }
+  }
+
+  // ---- combine the key splits: splits 1.. park (m, l, O^T) in LDS, split 0 folds them in
+  if (KS > 1) {
+    __syncthreads();  // all reads of the last tile are done: the tile buffers are reused
+    float4* slots = reinterpret_cast<float4*>(smem);
+    if (ksp > 0) {
+      float4* mine = slots + ((ksp - 1) * NRB + rb) * C::SLOT_F4 * 64 + lane;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq)
+          mine[(db * 4 + vq) * 64] = make_float4(o[db][4 * vq], o[db][4 * vq + 1], o[db][4 * vq + 2], o[db][4 * vq + 3]);
+      mine[(NDB * 4) * 64] = make_float4(m_run, l_run, 0.f, 0.f);
+    }
     __syncthreads();
+    if (ksp > 0) return;
+#pragma unroll 1
+    for (int sp = 1; sp < KS; ++sp) {
+      const float4* theirs = slots + ((sp - 1) * NRB + rb) * C::SLOT_F4 * 64 + lane;
+      const float4 st = theirs[(NDB * 4) * 64];
+      const float m_new = fmaxf(m_run, st.x);
+      const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+      const float wa = fast_exp2(m_run - m_ref), wb = fast_exp2(st.x - m_ref);  // exp2(-inf) = 0
+      l_run = l_run * wa + st.y * wb;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          const float4 x = theirs[(db * 4 + vq) * 64];
+          o[db][4 * vq + 0] = o[db][4 * vq + 0] * wa + x.x * wb;
+          o[db][4 * vq + 1] = o[db][4 * vq + 1] * wa + x.y * wb;
+          o[db][4 * vq + 2] = o[db][4 * vq + 2] * wa + x.z * wb;
+          o[db][4 * vq + 3] = o[db][4 * vq + 3] * wa + x.w * wb;
+        }
+      m_run = m_new;
+    }
   }
 
   // ---- normalise and store
@@ -302,16 +381,28 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(const FwdParams p) {
   }
 }
 
-int pick_gs(int G, int NW) {
+// number of q tiles of height bmh (rows per head) that have visible keys
+int64_t busy_tiles(const FwdParams& p, int bmh) {
+  int64_t n = 0;
+  for (int a = 0; a < p.g.nq; ++a) {
+    bool sees = false;
+    for (int kb = 0; kb < p.g.nk; ++kb) sees |= p.g.cls[a][kb] != LOONG_SKIP && p.g.k[kb].len > 0;
+    if (sees) n += (p.g.q[a].len + bmh - 1) / bmh;
+  }
+  return n;
+}
+
+int pick_gs(int G, int nrb) {
   for (int gs = 8; gs >= 1; gs >>= 1)
-    if (G % gs == 0 && gs <= NW) return gs;
+    if (G % gs == 0 && gs <= nrb) return gs;
   return 1;
 }
 
-template <int D, int NW, int BN>
+template <int D, int KS>
 int launch_cfg(FwdParams& p, hipStream_t st) {
-  p.GS = pick_gs(p.G, NW);
-  const int BMH = 32 * NW / p.GS;
+  constexpr int NRB = kFwdWaves / KS;
+  p.GS = pick_gs(p.G, NRB);
+  const int BMH = 32 * NRB / p.GS;
   p.tiles_total = 0;
   for (int a = 0; a < 2; ++a) {
     p.ntile[a] = a < p.g.nq ? (p.g.q[a].len + BMH - 1) / BMH : 0;
@@ -323,8 +414,24 @@ int launch_cfg(FwdParams& p, hipStream_t st) {
   if (total > 0x7ffffff0) return fail(LOONG_E_UNSUPPORTED, "forward grid too large");
   p.total_wg = (int)total;
   const unsigned grid = (unsigned)((total + 7) / 8 * 8);
-  fwd_kernel<D, NW, BN><<<dim3(grid), dim3(NW * 64), 0, st>>>(p);
+  fwd_kernel<D, KS><<<dim3(grid), dim3(kFwdWaves * 64), 0, st>>>(p);
   return check_launch("loong_attn_step_fwd (bf16)");
+}
+
+// Fewest key splits that still give (nearly) every CU a workgroup with work.  The
+// environment variable LOONG_FWD_KS (1, 2 or 4) overrides the choice (tuning aid).
+int pick_ks(const FwdParams& p) {
+  if (const char* e = std::getenv("LOONG_FWD_KS")) {
+    const int v = std::atoi(e);
+    if (v == 1 || v == 2 || v == 4) return v;
+  }
+  const int ks_opts[3] = {1, 2, 4};
+  for (int i = 0; i < 3; ++i) {
+    const int nrb = kFwdWaves / ks_opts[i], gs = pick_gs(p.G, nrb);
+    const int64_t n = busy_tiles(p, 32 * nrb / gs) * (p.Hq / gs) * p.B;
+    if (n >= 224) return ks_opts[i];
+  }
+  return 4;
 }
 
 }  // namespace
@@ -338,8 +445,15 @@ int launch_fwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
   for (int i = 0; i < 3; ++i) { p.qs[i] = d.q_stride[i]; p.ks[i] = d.kv_stride[i]; p.os[i] = d.o_stride[i]; }
   p.q_len = d.q_len; p.g = g; p.c = d.softmax_scale * kLog2e; p.fuse = (d.flags & LOONG_FUSE_MERGE) ? 1 : 0;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (d.head_dim == 128) return launch_cfg<128, 8, 64>(p, st);
-  return launch_cfg<64, 8, 64>(p, st);
+  const int ks = pick_ks(p);
+  if (d.head_dim == 128) {
+    if (ks == 1) return launch_cfg<128, 1>(p, st);
+    if (ks == 2) return launch_cfg<128, 2>(p, st);
+    return launch_cfg<128, 4>(p, st);
+  }
+  if (ks == 1) return launch_cfg<64, 1>(p, st);
+  if (ks == 2) return launch_cfg<64, 2>(p, st);
+  return launch_cfg<64, 4>(p, st);
 }
 
 }  // namespace loong

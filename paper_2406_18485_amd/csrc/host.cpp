@@ -59,6 +59,9 @@ int check_step(const loong_step_desc* d, StepGeom* g) {
     return fail(LOONG_E_SHAPE, "token stride of q/out is smaller than head_dim");
   if (d->kv_len > 0 && d->kv_stride[2] < d->head_dim)
     return fail(LOONG_E_SHAPE, "token stride of k/v is smaller than head_dim");
+  // the kernels address rows of one tile with 32-bit offsets from a 64-bit tile base
+  if (d->q_stride[2] >= (1 << 24) || d->kv_stride[2] >= (1 << 24) || d->o_stride[2] >= (1 << 24))
+    return fail(LOONG_E_UNSUPPORTED, "token strides must be below 2^24 elements");
   // keep every row index and every contiguous result offset far inside int64/int32 use
   if (!mul_ok((int64_t)d->batch * d->n_q_heads, (int64_t)d->q_len, (int64_t)1 << 40) ||
       d->q_len > (1 << 24) || d->kv_len > (1 << 24))
