@@ -79,6 +79,15 @@ struct FwdCfg {
   static_assert(KI >= 1 && KI * 1024 * kFwdWaves == TILE_B, "tile must split evenly over the waves");
 };
 
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands at
+// lds_addr + 16 l (lds_addr uniform over the wave).  Written as assembly so that the
+// compiler does not tie every later LDS read to the completion of all loads in flight;
+// the kernel waits for exactly the tile it needs with wait_vmcnt below.
+__device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_addr) {
+  const uint32_t uniform_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(uniform_addr) : "m0");
+}
+
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding)
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -184,6 +193,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
   const int ld_pos = lane % CH;
   const uint32_t k_piece = (uint32_t)(ld_pos ^ ((ld_row / RP) & (CH - 1))) * 16;
   const uint32_t v_piece = (uint32_t)(ld_pos ^ (((ld_row / RP) & (4 / RP - 1)) * 2)) * 16;
+  const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_t*)smem;  // LDS byte address of the buffers
   auto tile_of = [&](int t, int& kb, int& j0) {
     kb = t < ntk0 ? 0 : 1;
     j0 = (t - (kb ? ntk0 : 0)) * TK;
@@ -194,14 +204,14 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
     const int len = kb ? klen1 : klen0, start = kb ? kstart1 : kstart0;
     const int64_t tb = (int64_t)(start + j0) * rowbytes;
     const int last = len - 1 - j0;  // last valid row of the tile (>= 0); later rows repeat it
-    unsigned char* kl = smem + (t % NBUF) * C::BUF_B + wave * 1024;
-    unsigned char* vl = kl + C::TILE_B;
+    const uint32_t kl = smem_base + (t % NBUF) * C::BUF_B + wave * 1024;
+    const uint32_t vl = kl + C::TILE_B;
 #pragma unroll
     for (int i = 0; i < KI; ++i) {
       const int r = min(ld_row + i * 8 * C::RPI, last);
       const int64_t ro = tb + (int64_t)r * rowbytes;
-      __builtin_amdgcn_global_load_lds(kbase + ro + k_piece, (lds_void_t*)(kl + i * 8192), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(vbase + ro + v_piece, (lds_void_t*)(vl + i * 8192), 16, 0, 0);
+      load_to_lds_16(kbase + ro + k_piece, kl + i * 8192);
+      load_to_lds_16(vbase + ro + v_piece, vl + i * 8192);
     }
   };
 
@@ -236,7 +246,10 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
     return wave_live && j0 < klen && !(isdiag && j0 > wrow0 + 31);
   };
 
-  // ---- pipeline: PD tiles in flight
+  // ---- pipeline: PD tiles in flight.  Everything loaded so far (Q, running state) is waited
+  // for here, so that no counter wait of the compiler's own ends up inside the loop, where it
+  // would also wait for the tiles in flight.
+  wait_vmcnt<0>();
 #pragma unroll
   for (int t = 0; t < PD; ++t)
     if (t < total_t) issue_tile(t);
