@@ -431,18 +431,25 @@ int launch_cfg(FwdParams& p, hipStream_t st) {
   return check_launch("loong_attn_step_fwd (bf16)");
 }
 
-// Fewest key splits that still give (nearly) every CU a workgroup with work.  The
-// environment variable LOONG_FWD_KS (1, 2 or 4) overrides the choice (tuning aid).
-int pick_ks(const FwdParams& p) {
+// Key splits: more splits give more workgroups (each streams the whole visible K/V of its
+// head through its own LDS), so splitting pays only while the chip is under-filled.  When
+// one head's K/V chunk fits an XCD's L2 the aim is a workgroup on (nearly) every CU; when
+// it does not, the extra streams cost more than the idle CUs and half the CUs is enough.
+// The environment variable LOONG_FWD_KS (1, 2 or 4) overrides the choice (tuning aid).
+int pick_ks(const FwdParams& p, int head_dim) {
   if (const char* e = std::getenv("LOONG_FWD_KS")) {
     const int v = std::atoi(e);
     if (v == 1 || v == 2 || v == 4) return v;
   }
+  int64_t keys = 0;
+  for (int kb = 0; kb < p.g.nk; ++kb) keys += p.g.k[kb].len;
+  const int64_t kv_bytes = keys * head_dim * 2 * 2;
+  const int64_t want = kv_bytes <= (3 << 20) ? 224 : 112;
   const int ks_opts[3] = {1, 2, 4};
   for (int i = 0; i < 3; ++i) {
     const int nrb = kFwdWaves / ks_opts[i], gs = pick_gs(p.G, nrb);
     const int64_t n = busy_tiles(p, 32 * nrb / gs) * (p.Hq / gs) * p.B;
-    if (n >= 224) return ks_opts[i];
+    if (n >= want) return ks_opts[i];
   }
   return 4;
 }
@@ -458,7 +465,7 @@ int launch_fwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
   for (int i = 0; i < 3; ++i) { p.qs[i] = d.q_stride[i]; p.ks[i] = d.kv_stride[i]; p.os[i] = d.o_stride[i]; }
   p.q_len = d.q_len; p.g = g; p.c = d.softmax_scale * kLog2e; p.fuse = (d.flags & LOONG_FUSE_MERGE) ? 1 : 0;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int ks = pick_ks(p);
+  const int ks = pick_ks(p, d.head_dim);
   if (d.head_dim == 128) {
     if (ks == 1) return launch_cfg<128, 1>(p, st);
     if (ks == 2) return launch_cfg<128, 2>(p, st);
