@@ -42,4 +42,47 @@ __device__ __forceinline__ constexpr int acc_row(int v, int hh) { return 8 * (v 
 // Value of the lane 32 places away (wave64).
 __device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
 
+// ---- global memory -> LDS without registers -------------------------------------------------
+// 16 (or 4) bytes per lane from global memory straight into LDS: lane l's data lands at
+// lds_addr + 16 l (4 l), lds_addr uniform over the wave.  Written as assembly so that the
+// compiler does not tie every later LDS read to the completion of all loads in flight; the
+// kernels wait for the data they need with wait_vmcnt.
+__device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_addr) {
+  const uint32_t uniform_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(uniform_addr) : "m0");
+}
+__device__ __forceinline__ void load_to_lds_4(const void* gptr, uint32_t lds_addr) {
+  const uint32_t uniform_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(uniform_addr) : "m0");
+}
+
+// s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// Transposing LDS read: in every group of 16 lanes, lane i points at 8 bytes: row i / 4 of a
+// run of four rows, columns 4 (i % 4) .. +3 of a 16-column strip of 16-bit elements; it
+// receives the four rows' values of column i of the strip.
+typedef short v4i16_t __attribute__((ext_vector_type(4)));
+typedef short v8i16_t __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) v4i16_t lds_v4i16_t;
+__device__ __forceinline__ bf16x8_t read_tr_pair(const unsigned char* lo_run, const unsigned char* hi_run) {
+  const v4i16_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t*)lo_run);
+  const v4i16_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t*)hi_run);
+  return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// XOR applied to the 16-byte piece index of row `row` of an unpadded row-major bf16 tile in
+// LDS with D columns, chosen so that both access patterns of the kernels are free of bank
+// conflicts: 16 lanes reading the same piece of 16 consecutive rows, and 16 lanes of a
+// transposing read (four consecutive rows x two adjacent pieces).
+template <int D>
+__device__ __forceinline__ constexpr int tile_swizzle(int row) {
+  if (D == 128) return ((row & 3) << 1) | ((row >> 2) & 1) | (((row >> 3) & 1) << 3);
+  const int m = (row >> 1) & 7;  // D == 64: two rows per 256 bytes
+  return ((m & 1) << 1) | (((m >> 1) & 1) << 2) | ((m >> 2) & 1);
+}
+
 }  // namespace loong
