@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "device_utils.h"
 #include "loong_internal.h"
@@ -150,6 +151,11 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_kernel(const BwdParams p) 
   // rows (columns of the tile) 16 strip + 4 q .. +3 of block ib
   const uint32_t ds_rd = (4 * hh + tr_r) * C::DS_STR + (strip * 16 + tr_q * 4) * 2;
 
+  // dQ atomics: 32-bit offsets of this lane's 16 accumulator rows from the tile's first element
+  uint32_t dq_off[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) dq_off[v] = (uint32_t)(acc_row(v, hh) * p.os[2] + l32) * 4;
+
   // ---- the K columns this wave needs for dQ, as B operands [key][column] with the keys of
   // every 16-key slice in accumulator order: staged once through LDS, read transposed
   const int dq_ib = wave & 1, dq_db0 = (wave >> 1) * NDQ;  // this wave's piece of the dQ tile
@@ -221,54 +227,59 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_kernel(const BwdParams p) 
 
     // ---- S = Q K^T and dP = dO V^T: rows in registers, one key per lane
     floatx16_t s[NIB], dp[NIB];
+    {
+      floatx16_t zero;
 #pragma unroll
-    for (int ib = 0; ib < NIB; ++ib)
+      for (int v = 0; v < 16; ++v) zero[v] = 0.f;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) { s[ib][v] = 0.f; dp[ib][v] = 0.f; }
+      for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks)
+        for (int ib = 0; ib < NIB; ++ib) {
+          s[ib] = mfma32(as_bf16x8(*reinterpret_cast<const uint4*>(Qt + ib * 32 * ROWB + row_rd[ks])), kf[ks], ks ? s[ib] : zero);
+          dp[ib] = mfma32(as_bf16x8(*reinterpret_cast<const uint4*>(Ot + ib * 32 * ROWB + row_rd[ks])), vf[ks], ks ? dp[ib] : zero);
+        }
+    }
+
+    // ---- P = exp(S - LSE), dS = scale * P * (dP - delta); pack both; dS^T to LDS.
+    // (A row whose LSE is -inf sees no key in any step: such pairs are always masked.)
+    uint4 pp[NIB][2], pds[NIB][2];
+    auto probabilities = [&](auto masked) {
 #pragma unroll
       for (int ib = 0; ib < NIB; ++ib) {
-        s[ib] = mfma32(as_bf16x8(*reinterpret_cast<const uint4*>(Qt + ib * 32 * ROWB + row_rd[ks])), kf[ks], s[ib]);
-        dp[ib] = mfma32(as_bf16x8(*reinterpret_cast<const uint4*>(Ot + ib * 32 * ROWB + row_rd[ks])), vf[ks], dp[ib]);
-      }
-
-    // ---- P = exp(S - LSE), dS = scale * P * (dP - delta); pack both; dS^T to LDS
-    uint4 pp[NIB][2], pds[NIB][2];
+        float pe[16], de[16];
 #pragma unroll
-    for (int ib = 0; ib < NIB; ++ib) {
-      float pe[16], de[16];
+        for (int vq = 0; vq < 4; ++vq) {
+          const float4 L = *reinterpret_cast<const float4*>(&lse_s[ib * 32 + 8 * vq + 4 * hh]);
+          const float4 Dl = *reinterpret_cast<const float4*>(&dl_s[ib * 32 + 8 * vq + 4 * hh]);
+          const float Lr[4] = {L.x, L.y, L.z, L.w}, Dr[4] = {Dl.x, Dl.y, Dl.z, Dl.w};
 #pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        const float4 L = *reinterpret_cast<const float4*>(&lse_s[ib * 32 + 8 * vq + 4 * hh]);
-        const float4 Dl = *reinterpret_cast<const float4*>(&dl_s[ib * 32 + 8 * vq + 4 * hh]);
-        const float Lr[4] = {L.x, L.y, L.z, L.w}, Dr[4] = {Dl.x, Dl.y, Dl.z, Dl.w};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int v = 4 * vq + r;
-          // (a row whose LSE is -inf sees no key in any step: all its pairs are masked below)
-          float pv = fast_exp2(fmaf(s[ib][v], p.c, Lr[r] * -kLog2e));
-          if (need_mask) {
-            const int i_off = i0 + ib * 32 + acc_row(v, hh);
-            const bool ok = key_ok && i_off < qlen && (!isdiag || my_koff <= i_off);
-            pv = ok ? pv : 0.f;
+          for (int r = 0; r < 4; ++r) {
+            const int v = 4 * vq + r;
+            float pv = fast_exp2(fmaf(s[ib][v], p.c, Lr[r] * -kLog2e));
+            if (decltype(masked)::value) {
+              const int i_off = i0 + ib * 32 + acc_row(v, hh);
+              const bool ok = key_ok && i_off < qlen && (!isdiag || my_koff <= i_off);
+              pv = ok ? pv : 0.f;
+            }
+            pe[v] = pv;
+            de[v] = pv * (dp[ib][v] - Dr[r]) * p.scale;
           }
-          pe[v] = pv;
-          de[v] = pv * (dp[ib][v] - Dr[r]) * p.scale;
+        }
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) {
+          pp[ib][sl] = make_uint4(pack_bf16x2(pe[8 * sl + 0], pe[8 * sl + 1]), pack_bf16x2(pe[8 * sl + 2], pe[8 * sl + 3]),
+                                  pack_bf16x2(pe[8 * sl + 4], pe[8 * sl + 5]), pack_bf16x2(pe[8 * sl + 6], pe[8 * sl + 7]));
+          pds[ib][sl] = make_uint4(pack_bf16x2(de[8 * sl + 0], de[8 * sl + 1]), pack_bf16x2(de[8 * sl + 2], de[8 * sl + 3]),
+                                   pack_bf16x2(de[8 * sl + 4], de[8 * sl + 5]), pack_bf16x2(de[8 * sl + 6], de[8 * sl + 7]));
+          // dS^T tile, [key][row]: this lane's key row, rows acc_row(8 sl + 0..3) and (8 sl + 4..7)
+          unsigned char* drow = dst_lds + (32 * wave + l32) * C::DS_STR + (ib * 32 + 16 * sl + 4 * hh) * 2;
+          *reinterpret_cast<uint2*>(drow) = make_uint2(pds[ib][sl].x, pds[ib][sl].y);
+          *reinterpret_cast<uint2*>(drow + 16) = make_uint2(pds[ib][sl].z, pds[ib][sl].w);
         }
       }
-#pragma unroll
-      for (int sl = 0; sl < 2; ++sl) {
-        pp[ib][sl] = make_uint4(pack_bf16x2(pe[8 * sl + 0], pe[8 * sl + 1]), pack_bf16x2(pe[8 * sl + 2], pe[8 * sl + 3]),
-                                pack_bf16x2(pe[8 * sl + 4], pe[8 * sl + 5]), pack_bf16x2(pe[8 * sl + 6], pe[8 * sl + 7]));
-        pds[ib][sl] = make_uint4(pack_bf16x2(de[8 * sl + 0], de[8 * sl + 1]), pack_bf16x2(de[8 * sl + 2], de[8 * sl + 3]),
-                                 pack_bf16x2(de[8 * sl + 4], de[8 * sl + 5]), pack_bf16x2(de[8 * sl + 6], de[8 * sl + 7]));
-        // dS^T tile, [key][row]: this lane's key row, rows acc_row(8 sl + 0..3) and (8 sl + 4..7)
-        unsigned char* drow = dst_lds + (32 * wave + l32) * C::DS_STR + (ib * 32 + 16 * sl + 4 * hh) * 2;
-        *reinterpret_cast<uint2*>(drow) = make_uint2(pds[ib][sl].x, pds[ib][sl].y);
-        *reinterpret_cast<uint2*>(drow + 16) = make_uint2(pds[ib][sl].z, pds[ib][sl].w);
-      }
-    }
+    };
+    if (need_mask) probabilities(std::true_type{});
+    else probabilities(std::false_type{});
 
     // ---- dV += P^T dO, dK += dS^T Q: contraction over the tile's rows.  Element e of the A
     // operand is row 16 sl + 8 (e / 4) + 4 hh + e % 4 of block ib: the B operand is the run
@@ -302,14 +313,21 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_kernel(const BwdParams p) 
     // atomics, which share the counter with them and complete in no fixed order; nothing
     // ever waits for the atomics.
     wait_vmcnt<0>();
-    float* dq_base = p.dq + b * p.os[0] + h * p.os[1] + dq_db0 * 32 + l32;
+    unsigned char* dq_tile = reinterpret_cast<unsigned char*>(
+        p.dq + b * p.os[0] + h * p.os[1] + (int64_t)(qstart + i0 + dq_ib * 32) * p.os[2] + dq_db0 * 32);
+    if (i0 + BM <= qlen) {
 #pragma unroll
-    for (int n = 0; n < NDQ; ++n)
+      for (int n = 0; n < NDQ; ++n)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int i_off = i0 + dq_ib * 32 + acc_row(v, hh);
-        if (i_off < qlen) unsafeAtomicAdd(dq_base + (int64_t)(qstart + i_off) * p.os[2] + n * 32, dq[n][v]);
-      }
+        for (int v = 0; v < 16; ++v) unsafeAtomicAdd(reinterpret_cast<float*>(dq_tile + dq_off[v]) + n * 32, dq[n][v]);
+    } else {
+#pragma unroll
+      for (int n = 0; n < NDQ; ++n)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (i0 + dq_ib * 32 + acc_row(v, hh) < qlen)
+            unsafeAtomicAdd(reinterpret_cast<float*>(dq_tile + dq_off[v]) + n * 32, dq[n][v]);
+    }
   }
 
   // ---- dK (times the softmax scale's share already in dS), dV of this wave's 32 keys:
