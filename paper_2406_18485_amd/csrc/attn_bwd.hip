@@ -22,6 +22,8 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
+#include <cstring>
 #include <type_traits>
 
 #include "device_utils.h"
@@ -49,7 +51,7 @@ constexpr int kBwdWaves = 4;
 constexpr int kBwdBN = 32 * kBwdWaves;  // keys per workgroup
 constexpr int kBwdBM = 64;              // query rows per iteration
 
-template <int D>
+template <int D, bool WITH_DQ>
 struct BwdCfg {
   static constexpr int BM = kBwdBM, BN = kBwdBN;
   static constexpr int ROWB = D * 2;               // bytes per row of a Q / dO / K tile
@@ -59,16 +61,16 @@ struct BwdCfg {
   static constexpr int LI = QT_B / 1024 / kBwdWaves;  // loads per wave per Q (or dO) tile
   static constexpr int STAGE_B = 2 * QT_B + 2 * BM * 4;  // Q, dO, lse, delta
   static constexpr int DS_STR = BM * 2 + 16;       // bytes per key row of the dS^T tile (padded)
-  static constexpr int DS_B = BN * DS_STR;
+  static constexpr int DS_B = WITH_DQ ? BN * DS_STR : 0;
   static constexpr int KT_B = BN * ROWB;           // K tile staged once for the transposed fragments
-  static constexpr int STAGES_B = 2 * STAGE_B > KT_B ? 2 * STAGE_B : KT_B;
+  static constexpr int STAGES_B = (2 * STAGE_B > KT_B || !WITH_DQ) ? 2 * STAGE_B : KT_B;
   static constexpr int SMEM_BYTES = STAGES_B + DS_B;
   static constexpr int NDQ = D / 64;               // 32-column blocks of dQ per wave
 };
 
-template <int D>
+template <int D, bool WITH_DQ>
 __global__ __launch_bounds__(kBwdWaves * 64) void bwd_kernel(const BwdParams p) {
-  using C = BwdCfg<D>;
+  using C = BwdCfg<D, WITH_DQ>;
   constexpr int BM = C::BM, BN = C::BN, ROWB = C::ROWB, CH = C::CH, LI = C::LI, NDQ = C::NDQ;
   constexpr int NKS = D / 16, NDB = D / 32, NIB = BM / 32, NKSL = BN / 16;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[C::SMEM_BYTES];
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_kernel(const BwdParams p) 
   // every 16-key slice in accumulator order: staged once through LDS, read transposed
   const int dq_ib = wave & 1, dq_db0 = (wave >> 1) * NDQ;  // this wave's piece of the dQ tile
   bf16x8_t ktf[NDQ][NKSL];
-  {
+  if constexpr (WITH_DQ) {
     const unsigned char* kbase = reinterpret_cast<const unsigned char*>(p.k + b * p.ks[0] + hk * p.ks[1]);
     const int64_t rowbytes = p.ks[2] * 2;
     const int last = kseg.len - 1 - koff0;
@@ -272,9 +274,11 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_kernel(const BwdParams p) 
           pds[ib][sl] = make_uint4(pack_bf16x2(de[8 * sl + 0], de[8 * sl + 1]), pack_bf16x2(de[8 * sl + 2], de[8 * sl + 3]),
                                    pack_bf16x2(de[8 * sl + 4], de[8 * sl + 5]), pack_bf16x2(de[8 * sl + 6], de[8 * sl + 7]));
           // dS^T tile, [key][row]: this lane's key row, rows acc_row(8 sl + 0..3) and (8 sl + 4..7)
-          unsigned char* drow = dst_lds + (32 * wave + l32) * C::DS_STR + (ib * 32 + 16 * sl + 4 * hh) * 2;
-          *reinterpret_cast<uint2*>(drow) = make_uint2(pds[ib][sl].x, pds[ib][sl].y);
-          *reinterpret_cast<uint2*>(drow + 16) = make_uint2(pds[ib][sl].z, pds[ib][sl].w);
+          if constexpr (WITH_DQ) {
+            unsigned char* drow = dst_lds + (32 * wave + l32) * C::DS_STR + (ib * 32 + 16 * sl + 4 * hh) * 2;
+            *reinterpret_cast<uint2*>(drow) = make_uint2(pds[ib][sl].x, pds[ib][sl].y);
+            *reinterpret_cast<uint2*>(drow + 16) = make_uint2(pds[ib][sl].z, pds[ib][sl].w);
+          }
         }
       }
     };
@@ -294,6 +298,10 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_kernel(const BwdParams p) 
           dv[db] = mfma32(as_bf16x8(pp[ib][sl]), read_tr_pair(Ot + ro + tr_lo[db], Ot + ro + tr_hi[db]), dv[db]);
           dk[db] = mfma32(as_bf16x8(pds[ib][sl]), read_tr_pair(Qt + ro + tr_lo[db], Qt + ro + tr_hi[db]), dk[db]);
         }
+    if constexpr (!WITH_DQ) {
+      wait_vmcnt<0>();  // this wave's part of the next tile, issued a whole iteration ago
+      continue;
+    }
     __syncthreads();  // dS^T of all four waves visible
 
     // ---- dQ tile = dS K over the 128 keys; this wave: rows 32 dq_ib .., columns 32 dq_db0 ..
@@ -361,7 +369,7 @@ __global__ __launch_bounds__(256) void zero_kernel(int64_t n4, float4* a, float4
 }
 
 template <int D>
-int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
+int launch_d(BwdParams& p, bool accumulate, bool with_dq, hipStream_t st) {
   constexpr int BM = kBwdBM, BN = kBwdBN;
   p.kt_total = 0;
   for (int a = 0; a < 2; ++a) {
@@ -401,7 +409,8 @@ int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
     if (int rc = check_launch("loong_attn_step_bwd (clear dk/dv)")) return rc;
   }
   const unsigned grid = (unsigned)((total + 7) / 8 * 8);
-  bwd_kernel<D><<<dim3(grid), dim3(kBwdWaves * 64), 0, st>>>(p);
+  if (with_dq) bwd_kernel<D, true><<<dim3(grid), dim3(kBwdWaves * 64), 0, st>>>(p);
+  else bwd_kernel<D, false><<<dim3(grid), dim3(kBwdWaves * 64), 0, st>>>(p);
   return check_launch("loong_attn_step_bwd (bf16)");
 }
 
@@ -420,7 +429,13 @@ int launch_bwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
   p.g = g; p.scale = d.softmax_scale; p.c = d.softmax_scale * kLog2e;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bool accumulate = d.flags & LOONG_ACCUM_DKV;
-  return d.head_dim == 128 ? launch_d<128>(p, accumulate, st) : launch_d<64>(p, accumulate, st);
+  // dQ either from the same kernel (fp32 atomics) or from the row-owning pass that follows.
+  // LOONG_BWD_DQ=atomic selects the former (tuning aid).
+  const char* mode = std::getenv("LOONG_BWD_DQ");
+  const bool fused_dq = mode && std::strcmp(mode, "atomic") == 0;
+  const int rc = d.head_dim == 128 ? launch_d<128>(p, accumulate, fused_dq, st) : launch_d<64>(p, accumulate, fused_dq, st);
+  if (rc != LOONG_OK || fused_dq) return rc;
+  return launch_bwd_dq_bf16(d, g, q, k, v, d_o, lse, delta, dq, stream);
 }
 
 }  // namespace loong

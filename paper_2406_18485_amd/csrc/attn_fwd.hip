@@ -27,19 +27,16 @@
 // visited; only tiles touching the diagonal or a ragged end apply a mask.
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
-
 #include "device_utils.h"
 #include "loong_internal.h"
+#include "row_tiling.h"
 
 namespace loong {
 namespace {
 
 constexpr float kRescaleSlack = 8.f;  // the running maximum may lag the true one by 2^8
-constexpr int kFwdWaves = 8;
+constexpr int kFwdWaves = kRowWaves;
 
-typedef short v4i16_t __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) v4i16_t lds_v4i16_t;
 typedef __attribute__((address_space(3))) void lds_void_t;
 
 struct FwdParams {
@@ -78,21 +75,6 @@ struct FwdCfg {
   static constexpr int SMEM_BYTES = TILE_BYTES > COMB_BYTES ? TILE_BYTES : COMB_BYTES;
   static_assert(KI >= 1 && KI * 1024 * kFwdWaves == TILE_B, "tile must split evenly over the waves");
 };
-
-// 16 bytes per lane from global memory straight into LDS: lane l's data lands at
-// lds_addr + 16 l (lds_addr uniform over the wave).  Written as assembly so that the
-// compiler does not tie every later LDS read to the completion of all loads in flight;
-// the kernel waits for exactly the tile it needs with wait_vmcnt below.
-__device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_addr) {
-  const uint32_t uniform_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(uniform_addr) : "m0");
-}
-
-// s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding)
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
-}
 
 template <int D, int KS>
 __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) {
@@ -335,11 +317,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
           const unsigned char* vp = Vt + (jb * 32 + sl * 16) * ROWB + v_rd[db];
-          const v4i16_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t*)vp);
-          const v4i16_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t*)(vp + 8 * ROWB));
-          typedef short v8i16_t __attribute__((ext_vector_type(8)));
-          const v8i16_t a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[db] = mfma32(__builtin_bit_cast(bf16x8_t, a), as_bf16x8(pk[jb][sl]), o[db]);
+          o[db] = mfma32(read_tr_pair(vp, vp + 8 * ROWB), as_bf16x8(pk[jb][sl]), o[db]);
         }
   }
 
@@ -394,64 +372,18 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
   }
 }
 
-// number of q tiles of height bmh (rows per head) that have visible keys
-int64_t busy_tiles(const FwdParams& p, int bmh) {
-  int64_t n = 0;
-  for (int a = 0; a < p.g.nq; ++a) {
-    bool sees = false;
-    for (int kb = 0; kb < p.g.nk; ++kb) sees |= p.g.cls[a][kb] != LOONG_SKIP && p.g.k[kb].len > 0;
-    if (sees) n += (p.g.q[a].len + bmh - 1) / bmh;
-  }
-  return n;
-}
-
-int pick_gs(int G, int nrb) {
-  for (int gs = 8; gs >= 1; gs >>= 1)
-    if (G % gs == 0 && gs <= nrb) return gs;
-  return 1;
-}
-
 template <int D, int KS>
 int launch_cfg(FwdParams& p, hipStream_t st) {
-  constexpr int NRB = kFwdWaves / KS;
-  p.GS = pick_gs(p.G, NRB);
-  const int BMH = 32 * NRB / p.GS;
-  p.tiles_total = 0;
-  for (int a = 0; a < 2; ++a) {
-    p.ntile[a] = a < p.g.nq ? (p.g.q[a].len + BMH - 1) / BMH : 0;
-    p.tiles_total += p.ntile[a];
-  }
-  p.hgroups = p.Hq / p.GS;
-  const int64_t total = (int64_t)p.tiles_total * p.hgroups * p.B;
+  const RowTiling rt = make_row_tiling(p.g, p.G, p.Hq, p.B, kFwdWaves / KS);
+  p.GS = rt.GS; p.ntile[0] = rt.ntile[0]; p.ntile[1] = rt.ntile[1];
+  p.tiles_total = rt.tiles_total; p.hgroups = rt.hgroups;
+  const int64_t total = rt.total_wg;
   if (total == 0) return LOONG_OK;
   if (total > 0x7ffffff0) return fail(LOONG_E_UNSUPPORTED, "forward grid too large");
   p.total_wg = (int)total;
   const unsigned grid = (unsigned)((total + 7) / 8 * 8);
   fwd_kernel<D, KS><<<dim3(grid), dim3(kFwdWaves * 64), 0, st>>>(p);
   return check_launch("loong_attn_step_fwd (bf16)");
-}
-
-// Key splits: more splits give more workgroups (each streams the whole visible K/V of its
-// head through its own LDS), so splitting pays only while the chip is under-filled.  When
-// one head's K/V chunk fits an XCD's L2 the aim is a workgroup on (nearly) every CU; when
-// it does not, the extra streams cost more than the idle CUs and half the CUs is enough.
-// The environment variable LOONG_FWD_KS (1, 2 or 4) overrides the choice (tuning aid).
-int pick_ks(const FwdParams& p, int head_dim) {
-  if (const char* e = std::getenv("LOONG_FWD_KS")) {
-    const int v = std::atoi(e);
-    if (v == 1 || v == 2 || v == 4) return v;
-  }
-  int64_t keys = 0;
-  for (int kb = 0; kb < p.g.nk; ++kb) keys += p.g.k[kb].len;
-  const int64_t kv_bytes = keys * head_dim * 2 * 2;
-  const int64_t want = kv_bytes <= (3 << 20) ? 224 : 112;
-  const int ks_opts[3] = {1, 2, 4};
-  for (int i = 0; i < 3; ++i) {
-    const int nrb = kFwdWaves / ks_opts[i], gs = pick_gs(p.G, nrb);
-    const int64_t n = busy_tiles(p, 32 * nrb / gs) * (p.Hq / gs) * p.B;
-    if (n >= want) return ks_opts[i];
-  }
-  return 4;
 }
 
 }  // namespace
@@ -465,7 +397,8 @@ int launch_fwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
   for (int i = 0; i < 3; ++i) { p.qs[i] = d.q_stride[i]; p.ks[i] = d.kv_stride[i]; p.os[i] = d.o_stride[i]; }
   p.q_len = d.q_len; p.g = g; p.c = d.softmax_scale * kLog2e; p.fuse = (d.flags & LOONG_FUSE_MERGE) ? 1 : 0;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int ks = pick_ks(p, d.head_dim);
+  // LOONG_FWD_KS (1, 2 or 4) overrides the number of key splits (tuning aid)
+  const int ks = pick_key_splits(g, p.G, p.Hq, p.B, d.head_dim, "LOONG_FWD_KS");
   if (d.head_dim == 128) {
     if (ks == 1) return launch_cfg<128, 1>(p, st);
     if (ks == 2) return launch_cfg<128, 2>(p, st);
