@@ -56,6 +56,18 @@ __device__ __forceinline__ void load_to_lds_4(const void* gptr, uint32_t lds_add
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(uniform_addr) : "m0");
 }
 
+// The same with the address split into a wave-uniform 64-bit base (scalar registers) and a
+// 32-bit per-lane byte offset: no 64-bit vector arithmetic per load.
+__device__ __forceinline__ void load_to_lds_16(const void* uniform_base, uint32_t lane_off, uint32_t lds_addr) {
+  const uint64_t a = reinterpret_cast<uint64_t>(uniform_base);
+  // (the builtin returns a signed int: convert each half back to unsigned before widening)
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)a);
+  const uint64_t base = ((uint64_t)hi << 32) | (uint64_t)lo;
+  const uint32_t uniform_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(uniform_addr) : "m0");
+}
+
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding)
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
