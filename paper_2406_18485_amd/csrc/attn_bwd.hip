@@ -202,6 +202,10 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
 
   int stage = 0;
   for (int it = it_begin; it < it_end; ++it, stage ^= 1, advance(cur)) {
+    // the accumulators live in the accumulation registers for the whole loop (a hint: nothing
+    // is emitted here, but the register allocator may not park them among the vector registers)
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) asm volatile("" : "+a"(dk[db]), "+a"(dv[db]));
     __syncthreads();  // tile `it` is in LDS (each wave waited for its part); iteration it - 1 is finished
     if (it + 1 < it_end) {
       advance(nxt);
@@ -220,11 +224,12 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
     // One tile.  Block ib = rows 32 ib .. 32 ib + 31; register v of an accumulator is row
     // acc_row(v, hh) of the block.  The tile is a sequence of 4 NS matrix steps: S and T of
     // block 0 (alternating), of block 1, then dV and dK with block 0, with block 1; the
-    // LDS operand of step k + PF is requested before step k is issued, and the element-wise
-    // work on block 0 (1) is spread over the steps of the second (third) quarter.
+    // LDS operands are requested a batch of PF steps ahead (one counter wait per batch), and
+    // the element-wise work on block 0 (1) is spread over the steps of the second (third)
+    // quarter.
     constexpr int NS = 2 * NKS;    // matrix steps per quarter (== 4 * NDB)
     constexpr int EPS = 16 / NS;   // elements per matrix step
-    constexpr int PF = 3;          // operand prefetch distance, in matrix steps
+    constexpr int PF = 4;          // operands are read in batches of PF, one batch ahead of their use
     static_assert(NS == 4 * NDB && EPS * NS == 16, "quarters of equal length");
     floatx16_t s[2], t[2];
     float nl[2][16];
@@ -291,20 +296,21 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
         e_even = ev;
       }
     };
-    bf16x8_t ring[PF + 1];
-#pragma unroll
-    for (int k = 0; k < PF; ++k) ring[k] = operand(k);
-#pragma unroll
-    for (int k = 0; k < 4 * NS; ++k) {
-      if (k + PF < 4 * NS) ring[(k + PF) % (PF + 1)] = operand(k + PF);
-      matrix_step(k, ring[k % (PF + 1)]);
-      const int quarter = k / NS, j = k % NS;
-      if (quarter == 1 || quarter == 2) {
-#pragma unroll
-        for (int u = 0; u < EPS; ++u) element(quarter - 1, j * EPS + u);
+    bf16x8_t ring[2 * PF];
+    static_for<0, PF>([&](auto kc) { ring[kc.value] = operand(kc.value); });
+    static_for<0, 4 * NS>([&](auto kc) {
+      constexpr int k = decltype(kc)::value;
+      if constexpr (k % PF == 0) {
+        static_for<k + PF, (k + 2 * PF < 4 * NS ? k + 2 * PF : 4 * NS)>(
+            [&](auto nc) { ring[nc.value % (2 * PF)] = operand(nc.value); });
       }
-      __builtin_amdgcn_sched_barrier(0);  // keep the operand reads PF steps ahead of their use
-    }
+      matrix_step(k, ring[k % (2 * PF)]);
+      constexpr int quarter = k / NS, j = k % NS;
+      if constexpr (quarter == 1 || quarter == 2) {
+        static_for<0, EPS>([&](auto uc) { element(quarter - 1, j * EPS + uc.value); });
+      }
+      __builtin_amdgcn_sched_barrier(0);  // keep the operand reads ahead of their use
+    });
     wait_vmcnt<0>();  // this wave's part of the next tile, issued a whole iteration ago
   }
 

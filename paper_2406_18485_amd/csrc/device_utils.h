@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace loong {
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -95,6 +97,16 @@ __device__ __forceinline__ constexpr int tile_swizzle(int row) {
   if (D == 128) return ((row & 3) << 1) | ((row >> 2) & 1) | (((row >> 3) & 1) << 3);
   const int m = (row >> 1) & 7;  // D == 64: two rows per 256 bytes
   return ((m & 1) << 1) | (((m >> 1) & 1) << 2) | ((m >> 2) & 1);
+}
+
+// f(integral_constant<int, I>) for I = First .. Last - 1, unrolled by instantiation (does not
+// depend on the loop unroller's size limits)
+template <int First, int Last, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (First < Last) {
+    f(std::integral_constant<int, First>{});
+    static_for<First + 1, Last>(f);
+  }
 }
 
 }  // namespace loong
