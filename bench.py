@@ -7,8 +7,9 @@ every K/V chunk resident in HBM, launches back to back on one stream.
 
 Prints ONE JSON line: fwd+bwd TFLOP/s (14*d FLOP per visible (query, key) pair per q
 head: 4d forward, 10d backward including the recomputation the method needs), the MFMA
-roofline of the dominant kernel (the backward step), and the fp64 oracle timed on the
-host cores on a bounded sample of the same workload.
+roofline of the dominant kernel (the dK/dV kernel of the backward step, timed with events
+around each launch), and the fp64 oracle timed on the host cores on a bounded sample of the
+same workload.
 """
 from __future__ import annotations
 
@@ -23,6 +24,11 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script (summaries under profiles/), scaled by the same counters' reading for a copy kernel
+# of known size; null for workloads that were not profiled.
+TRAFFIC: dict = {"mha7b_32k": 64.4e6}  # 25.5 MiB read + 36.0 MiB written per bwd_dkv launch
 
 
 def pairs_per_head(cfg) -> int:
@@ -61,6 +67,8 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into workloads.CONFIGS (1 = 7B MHA shard, 32K)")
     ap.add_argument("--cpu-rows", type=int, default=512, help="rows of the oracle sample (0: skip the CPU baseline)")
     ap.add_argument("--unfused", action="store_true", help="run Attention and Update as separate kernels")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="launch only device-to-device copies of 256 MiB (reference for the HBM byte counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures the per-device ring step on ONE GPU; --gpus > 1 is not part of this build "
@@ -73,33 +81,58 @@ def main():
 
     cfg = CONFIGS[args.config]
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.copy_calibration:
+        # one elementwise copy kernel reads 256 MiB and writes 256 MiB per launch
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(8):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read_per_launch": src.numel() * 4,
+                                               "bytes_written_per_launch": src.numel() * 4, "launches": 8}}))
+        return
     inp = make_inputs(cfg)
     run = Replayed(cfg, inp)
     rep, s = run.rep, run.rep.shape
     fuse = not args.unfused
 
     def one_pass(ev=None):
+        if ev:
+            ev["fwd0"].record()
         rep.forward(run.q, run.k_by_src, run.v_by_src, fuse_merge=fuse)
+        if ev:
+            ev["fwd1"].record()
         desc0 = P.make_desc(batch=1, n_q_heads=s.hq, n_kv_heads=s.hkv, head_dim=s.d, q_len=s.L, kv_len=s.L,
                             dtype=s.dtype, softmax_scale=s.scale)
         P.bwd_delta(desc0, rep.o, run.d_o, rep.delta)
         rep.dq.zero_()
-        if ev:
-            ev[0].record()
-        for step in rep.plan:
+        for i, step in enumerate(rep.plan):
             src = step["src_rank"]
             d = P.make_desc(batch=1, n_q_heads=s.hq, n_kv_heads=s.hkv, head_dim=s.d, q_len=s.L, kv_len=s.L,
                             dtype=s.dtype, softmax_scale=s.scale, causal=True, chunk_len=s.c,
                             q_chunk=step["q_chunk"], kv_chunk=step["kv_chunk"])
+            # the backward micro-step is two kernels; issued one by one so that each can be timed
+            if ev:
+                ev["bwd"][i][0].record()
+            d.flags = P.BWD_ONLY_DKV
             P.attn_step_bwd(d, run.q, run.k_by_src[src], run.v_by_src[src], None, run.d_o, rep.lse, rep.delta,
-                            rep.dq, rep.dk[src], rep.dv[src])
-        if ev:
-            ev[1].record()
+                            None, rep.dk[src], rep.dv[src])
+            if ev:
+                ev["bwd"][i][1].record()
+            d.flags = P.BWD_ONLY_DQ
+            P.attn_step_bwd(d, run.q, run.k_by_src[src], run.v_by_src[src], None, run.d_o, rep.lse, rep.delta,
+                            rep.dq, None, None)
+            if ev:
+                ev["bwd"][i][2].record()
+
+    def new_events():
+        E = lambda: torch.cuda.Event(enable_timing=True)
+        return {"fwd0": E(), "fwd1": E(), "bwd": [(E(), E(), E()) for _ in rep.plan]}
 
     for _ in range(args.warmup):
         one_pass()
     torch.cuda.synchronize()
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    events = [new_events() for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
         one_pass(events[i])
@@ -109,9 +142,20 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     pairs = pairs_per_head(cfg) * cfg.hq
     tflops = 14.0 * cfg.d * pairs / (dt / args.steps) / 1e12
-    bwd_ms = sum(a.elapsed_time(b) for a, b in events) / args.steps          # cp backward launches
-    bwd_launch_ms = bwd_ms / cfg.cp
-    bwd_tflops = 10.0 * cfg.d * pairs / cfg.cp / (bwd_launch_ms * 1e-3) / 1e12
+    fwd_ms = sum(e["fwd0"].elapsed_time(e["fwd1"]) for e in events) / args.steps
+    dkv_ms = sum(a.elapsed_time(b) for e in events for a, b, _ in e["bwd"]) / args.steps
+    dq_ms = sum(b.elapsed_time(c) for e in events for _, b, c in e["bwd"]) / args.steps
+    bwd_ms = dkv_ms + dq_ms
+    # dominant kernel: the dK/dV kernel of the backward micro-step.  Its algorithmic work is
+    # four of the backward's five matrix products (S, dP, dV, dK): 8*d FLOP per visible pair.
+    dkv_tflops = 8.0 * cfg.d * pairs / (dkv_ms * 1e-3) / 1e12
+    per_kernel = {
+        "fwd_kernel": {"flop_per_pair": "4*d", "avg_launch_ms": round(fwd_ms / cfg.cp, 4),
+                       "tflops": round(4.0 * cfg.d * pairs / (fwd_ms * 1e-3) / 1e12, 1)},
+        "bwd_dkv_kernel": {"flop_per_pair": "8*d", "avg_launch_ms": round(dkv_ms / cfg.cp, 4), "tflops": round(dkv_tflops, 1)},
+        "dq_kernel": {"flop_per_pair": "6*d (S and dP recomputed)", "avg_launch_ms": round(dq_ms / cfg.cp, 4),
+                      "tflops": round(6.0 * cfg.d * pairs / (dq_ms * 1e-3) / 1e12, 1)},
+    }
     result = {
         "metric": "fwd+bwd ring-step attention TFLOP/s on 1 GPU; % of bf16 MFMA peak",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -123,11 +167,13 @@ def main():
                    "flop_convention": "14*d per visible pair per q head (4d fwd + 10d bwd)"},
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "tflops_12d_convention": round(tflops * 12.0 / 14.0, 2),
-        "roofline": {"bound": "mfma", "kernel": "bwd_kernel (one backward micro-step)",
-                     "achieved": round(bwd_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(bwd_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                     "avg_launch_ms": round(bwd_launch_ms, 4), "launches_per_step": cfg.cp},
-        "fwd_ms": round(ms_per_step - bwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
+        "roofline": {"bound": "mfma", "kernel": "bwd_dkv_kernel (dK/dV half of one backward micro-step)",
+                     "achieved": round(dkv_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(dkv_tflops / PEAK_BF16_TFLOPS, 4), "traffic": TRAFFIC.get(cfg.name),
+                     "avg_launch_ms": round(dkv_ms / cfg.cp, 4), "launches_per_step": cfg.cp,
+                     "flop_per_launch": round(8.0 * cfg.d * pairs / cfg.cp)},
+        "kernels": per_kernel,
+        "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
     }
     if args.cpu_rows > 0:
         result["cpu_baseline"] = cpu_baseline(cfg, inp, args.cpu_rows)

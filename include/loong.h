@@ -59,6 +59,8 @@ extern "C" {
 #define LOONG_FUSE_MERGE     1    /* fwd: out/lse hold the running result; the step is merged in-kernel */
 #define LOONG_ACCUM_DKV      2    /* bwd: dk/dv are added to instead of overwritten */
 #define LOONG_COMPUTE_DELTA  4    /* bwd: fill `delta` from o and d_o before the step */
+#define LOONG_BWD_ONLY_DKV   8    /* bwd: compute dk/dv only (dq may be NULL and is not touched) */
+#define LOONG_BWD_ONLY_DQ    16   /* bwd: compute this step's share of dq only (dk, dv may be NULL) */
 
 typedef struct loong_step_desc {
   int32_t batch;
@@ -126,8 +128,12 @@ LOONG_API int loong_lse_merge(int64_t rows, int32_t head_dim, float* out, float*
  * With LOONG_COMPUTE_DELTA, `o` (stored output, same type/strides as q) must be given and
  * delta is written first; otherwise `o` may be NULL.
  * Outputs: dq [B,Hq,q_len,d] fp32 (o_stride) is ADDED to (zero it before the first
- * step; fp32 atomics: order of additions is not fixed); dk, dv fp32 contiguous
- * [B,Hkv,kv_len,d] are overwritten, or added to with LOONG_ACCUM_DKV.
+ * step); every row is updated by one thread group in a fixed order, so dq is
+ * bit-reproducible.  dk, dv fp32 contiguous [B,Hkv,kv_len,d] are overwritten, or added to
+ * with LOONG_ACCUM_DKV (then, and when a step has too few key tiles to fill the chip and
+ * its query loop is split, they are accumulated with fp32 atomics in no fixed order).
+ * The two halves run as two kernels on `stream`; LOONG_BWD_ONLY_DKV / LOONG_BWD_ONLY_DQ
+ * run one of them (both flags together: LOONG_E_UNSUPPORTED).
  */
 LOONG_API int loong_attn_step_bwd(const loong_step_desc* desc, const void* q, const void* k, const void* v,
                         const void* o, const void* d_o, const float* lse, float* delta,

@@ -26,12 +26,15 @@ int loong_attn_step_bwd(const loong_step_desc* desc, const void* q, const void* 
   clear_error();
   StepGeom g;
   if (int rc = check_step(desc, &g)) return rc;
-  if (!q || !k || !v || !d_o || !lse || !delta || !dq || !dk || !dv)
+  const bool only_dkv = desc->flags & LOONG_BWD_ONLY_DKV, only_dq = desc->flags & LOONG_BWD_ONLY_DQ;
+  if (only_dkv && only_dq)
+    return fail(LOONG_E_UNSUPPORTED, "loong_attn_step_bwd: LOONG_BWD_ONLY_DKV and LOONG_BWD_ONLY_DQ exclude each other");
+  if (!q || !k || !v || !d_o || !lse || !delta || (!only_dkv && !dq) || (!only_dq && (!dk || !dv)))
     return fail(LOONG_E_NULL, "loong_attn_step_bwd: NULL tensor");
   const bool want_delta = desc->flags & LOONG_COMPUTE_DELTA;
   if (want_delta && !o) return fail(LOONG_E_NULL, "loong_attn_step_bwd: LOONG_COMPUTE_DELTA needs o");
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) ||
-      !aligned16(dk) || !aligned16(dv) || (want_delta && !aligned16(o)))
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || (!only_dkv && !aligned16(dq)) ||
+      (!only_dq && (!aligned16(dk) || !aligned16(dv))) || (want_delta && !aligned16(o)))
     return fail(LOONG_E_ALIGN, "loong_attn_step_bwd: tensors must be 16-byte aligned");
   if (desc->batch == 0) return LOONG_OK;
   if (want_delta)

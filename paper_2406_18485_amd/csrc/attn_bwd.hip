@@ -405,8 +405,11 @@ int launch_bwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
   p.g = g; p.scale = d.softmax_scale; p.c = d.softmax_scale * kLog2e;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bool accumulate = d.flags & LOONG_ACCUM_DKV;
-  const int rc = d.head_dim == 128 ? launch_d<128>(p, accumulate, st) : launch_d<64>(p, accumulate, st);
-  if (rc != LOONG_OK) return rc;
+  if (!(d.flags & LOONG_BWD_ONLY_DQ)) {
+    const int rc = d.head_dim == 128 ? launch_d<128>(p, accumulate, st) : launch_d<64>(p, accumulate, st);
+    if (rc != LOONG_OK) return rc;
+  }
+  if (d.flags & LOONG_BWD_ONLY_DKV) return LOONG_OK;
   return launch_bwd_dq_bf16(d, g, q, k, v, d_o, lse, delta, dq, stream);
 }
 

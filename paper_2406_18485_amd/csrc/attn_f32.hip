@@ -261,11 +261,12 @@ int launch_bwd_f32(const loong_step_desc& d, const StepGeom& g, const void* q, c
   p.q = (const float*)q; p.k = (const float*)k; p.v = (const float*)v; p.d_o = (const float*)d_o;
   p.lse_in = lse; p.delta = delta; p.dq = dq; p.dk = dk; p.dv = dv;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (qrows > 0 && krows > 0) {
+  const bool do_dq = !(d.flags & LOONG_BWD_ONLY_DKV), do_dkv = !(d.flags & LOONG_BWD_ONLY_DQ);
+  if (do_dq && qrows > 0 && krows > 0) {
     bwd_dq_f32_kernel<<<dim3((unsigned)qrows), dim3(64), 0, st>>>(p);
     if (int rc = check_launch("loong_attn_step_bwd (fp32 dq)")) return rc;
   }
-  if (krows > 0) {
+  if (do_dkv && krows > 0) {
     bwd_dkv_f32_kernel<<<dim3((unsigned)krows), dim3(64), 0, st>>>(p);
     if (int rc = check_launch("loong_attn_step_bwd (fp32 dk/dv)")) return rc;
   }

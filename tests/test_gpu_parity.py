@@ -217,6 +217,43 @@ def test_token_major_strides_and_accumulating_dkv(dtype):
     _direct(dtype, 2, 4, 2, 64, 130, 190, seed=3, strided=True, accum=True)
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 32)])
+def test_one_sided_backward_flags_split_the_step_exactly(dtype, d):
+    """dK/dV-only then dQ-only must reproduce the full call and leave the other side untouched."""
+    b, hq, hkv, nq, nk = 1, 4, 2, 200, 330
+    rng = np.random.default_rng(11)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    mk = lambda *s: torch.from_numpy(rng.standard_normal(s).astype(np.float32) * 0.5).to(DEV).to(tdt)
+    q, do, o = mk(b, hq, nq, d), mk(b, hq, nq, d), mk(b, hq, nq, d)
+    k, v = mk(b, hkv, nk, d), mk(b, hkv, nk, d)
+    lse = torch.from_numpy(rng.uniform(3.0, 5.0, (b, hq, nq)).astype(np.float32)).to(DEV)
+    desc = P.make_desc(batch=b, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, q_len=nq, kv_len=nk,
+                       dtype=P.BF16 if dtype == "bf16" else P.FP32, softmax_scale=1.0 / np.sqrt(d))
+    res = []
+    for split in (False, True):
+        delta = torch.empty(b, hq, nq, device=DEV)
+        dq = torch.full((b, hq, nq, d), 0.25, device=DEV)
+        dk, dv = torch.full((b, hkv, nk, d), 9.0, device=DEV), torch.full((b, hkv, nk, d), 9.0, device=DEV)
+        if not split:
+            desc.flags = P.COMPUTE_DELTA
+            P.attn_step_bwd(desc, q, k, v, o, do, lse, delta, dq, dk, dv)
+        else:
+            desc.flags = P.COMPUTE_DELTA | P.BWD_ONLY_DKV
+            P.attn_step_bwd(desc, q, k, v, o, do, lse, delta, None, dk, dv)
+            torch.cuda.synchronize()
+            assert torch.all(dq == 0.25)
+            keep = dk.clone()
+            desc.flags = P.BWD_ONLY_DQ
+            P.attn_step_bwd(desc, q, k, v, None, do, lse, delta, dq, None, None)
+            torch.cuda.synchronize()
+            assert torch.equal(dk, keep)
+        torch.cuda.synchronize()
+        res.append((dq.clone(), dk.clone(), dv.clone()))
+    assert torch.equal(res[0][0], res[1][0])          # dq: fixed order of additions
+    for a, c in zip(res[0][1:], res[1][1:]):          # dk, dv: split query loops add with atomics
+        assert torch.allclose(a, c, rtol=0, atol=1e-3)
+
+
 def test_q_len_zero_is_a_noop():
     desc = P.make_desc(batch=1, n_q_heads=2, n_kv_heads=2, head_dim=128, q_len=0, kv_len=64, dtype=P.BF16, softmax_scale=0.1)
     x = torch.zeros(1, 2, 64, 128, dtype=torch.bfloat16, device=DEV)

@@ -111,6 +111,15 @@ def test_entry_points_fail_before_any_launch_on_bad_arguments():
     assert lib.loong_attn_step_fwd(C.byref(_good(batch=0)), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, None) == P.OK
     dd = _good(flags=P.COMPUTE_DELTA)
     assert lib.loong_attn_step_bwd(C.byref(dd), 16, 16, 16, None, 16, 16, 16, 16, 16, 16, None) == P.E_NULL
+    # the one-sided backward flags: exclusive, and each lifts the NULL check of the other side's outputs only
+    both = _good(flags=P.BWD_ONLY_DKV | P.BWD_ONLY_DQ)
+    assert lib.loong_attn_step_bwd(C.byref(both), *([0x1000] * 10), None) == P.E_UNSUPPORTED
+    z = _good(batch=0, flags=P.BWD_ONLY_DKV)
+    assert lib.loong_attn_step_bwd(C.byref(z), 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, None) == P.OK
+    assert lib.loong_attn_step_bwd(C.byref(z), 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, None, None, 0x1000, None) == P.E_NULL
+    z = _good(batch=0, flags=P.BWD_ONLY_DQ)
+    assert lib.loong_attn_step_bwd(C.byref(z), 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, 0x1000, None, None, None) == P.OK
+    assert lib.loong_attn_step_bwd(C.byref(z), 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, None, None, None, None) == P.E_NULL
 
 
 def test_error_text_is_per_call():
