@@ -348,27 +348,25 @@ __global__ __launch_bounds__(256) void zero_kernel(int64_t n4, float4* a, float4
 template <int D>
 int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
   constexpr int BM = kBwdBM, BN = kBwdBN;
+  // Only key tiles that some query can see are listed (eight equal ranges of the list, one
+  // per XCD, then carry equal work); key segments nobody sees are cleared by the zero pass.
+  // The query-tile loop is spread over several workgroups when the listed tiles are fewer
+  // than the CUs, and once more when a diagonal block makes their loop lengths uneven.
   p.kt_total = 0;
-  for (int a = 0; a < 2; ++a) {
-    p.nkt[a] = a < p.g.nk ? (p.g.k[a].len + BN - 1) / BN : 0;
-    p.kt_total += p.nkt[a];
+  bool diag = false, unseen_keys = false;
+  for (int kb = 0; kb < 2; ++kb) {
+    bool seen = false;
+    if (kb < p.g.nk)
+      for (int a = 0; a < p.g.nq; ++a) {
+        seen |= p.g.cls[a][kb] != LOONG_SKIP && p.g.q[a].len > 0;
+        diag |= p.g.cls[a][kb] == LOONG_DIAG;
+      }
+    p.nkt[kb] = seen ? (p.g.k[kb].len + BN - 1) / BN : 0;
+    p.kt_total += p.nkt[kb];
+    unseen_keys |= kb < p.g.nk && !seen && p.g.k[kb].len > 0;
   }
   const int64_t base = (int64_t)p.kt_total * p.Hkv * p.B;
-  if (base == 0) return LOONG_OK;
-  // Key tiles that some query can see; the query-tile loop is spread over several workgroups
-  // when those are fewer than the CUs, and once more when a diagonal block makes their
-  // loop lengths uneven.
-  int64_t busy = 0;
-  bool diag = false;
-  for (int kb = 0; kb < p.g.nk; ++kb) {
-    bool seen = false;
-    for (int a = 0; a < p.g.nq; ++a) {
-      seen |= p.g.cls[a][kb] != LOONG_SKIP && p.g.q[a].len > 0;
-      diag |= p.g.cls[a][kb] == LOONG_DIAG;
-    }
-    if (seen) busy += p.nkt[kb];
-  }
-  busy *= (int64_t)p.Hkv * p.B;
+  const int64_t busy = base;
   int nsplit = 1;
   const int64_t q_tiles = std::max<int64_t>((int64_t)p.G * ((p.q_len + BM - 1) / BM), 1);
   if (busy > 0 && busy < 256) nsplit = (int)std::min<int64_t>((256 + busy - 1) / busy, 16);
@@ -379,12 +377,13 @@ int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
   const int64_t total = base * nsplit;
   if (total > 0x7ffffff0) return fail(LOONG_E_UNSUPPORTED, "backward grid too large");
   p.total_wg = (int)total;
-  if (nsplit > 1 && !accumulate) {
+  if ((nsplit > 1 || unseen_keys) && !accumulate) {
     const int64_t n4 = (int64_t)p.B * p.Hkv * p.kv_len * D / 4;
     zero_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st>>>(n4, reinterpret_cast<float4*>(p.dk),
                                                                           reinterpret_cast<float4*>(p.dv));
     if (int rc = check_launch("loong_attn_step_bwd (clear dk/dv)")) return rc;
   }
+  if (total == 0) return LOONG_OK;
   const unsigned grid = (unsigned)((total + 7) / 8 * 8);
   bwd_dkv_kernel<D><<<dim3(grid), dim3(kBwdWaves * 64), 0, st>>>(p);
   return check_launch("loong_attn_step_bwd (bf16, dK/dV)");

@@ -142,20 +142,34 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
     kb = t < ntk0 ? 0 : 1;
     j0 = (t - (kb ? ntk0 : 0)) * TK;
   };
+  // byte offsets of this lane's pieces from the first row of a tile (full tiles only; the
+  // 32-bit form needs TK rows to span less than 4 GiB, else every tile takes the general path)
+  const bool narrow = rowbytes * TK < (int64_t(1) << 32);
+  uint32_t ld_off[KI];
+#pragma unroll
+  for (int i = 0; i < KI; ++i) ld_off[i] = (uint32_t)(ld_row + i * 8 * C::RPI) * (uint32_t)rowbytes + ld_piece;
   auto issue_tile = [&](int t) {
     int kb, j0;
     tile_of(t, kb, j0);
     const int len = kb ? klen1 : klen0, start = kb ? kstart1 : kstart0;
-    const int64_t tb = (int64_t)(start + j0) * rowbytes + ld_piece;
+    const int64_t tb = (int64_t)(start + j0) * rowbytes;
     const int last = len - 1 - j0;  // last valid row of the tile (>= 0); later rows repeat it
     const uint32_t kl = smem_base + (t % NBUF) * C::BUF_B + wave * 1024;
     const uint32_t vl = kl + C::TILE_B;
+    if (narrow && last >= TK - 1) {  // whole tile: uniform base in scalar registers + per-lane offset
 #pragma unroll
-    for (int i = 0; i < KI; ++i) {
-      const int r = min(ld_row + i * 8 * C::RPI, last);
-      const int64_t ro = tb + (int64_t)r * rowbytes;
-      load_to_lds_16(kbase + ro, kl + i * 8192);
-      load_to_lds_16(vbase + ro, vl + i * 8192);
+      for (int i = 0; i < KI; ++i) {
+        load_to_lds_16(kbase + tb, ld_off[i], kl + i * 8192);
+        load_to_lds_16(vbase + tb, ld_off[i], vl + i * 8192);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < KI; ++i) {
+        const int r = min(ld_row + i * 8 * C::RPI, last);
+        const int64_t ro = tb + (int64_t)r * rowbytes + ld_piece;
+        load_to_lds_16(kbase + ro, kl + i * 8192);
+        load_to_lds_16(vbase + ro, vl + i * 8192);
+      }
     }
   };
 
@@ -299,7 +313,7 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
 
 template <int D, int KS>
 int launch_cfg(DqParams& p, hipStream_t st) {
-  const RowTiling rt = make_row_tiling(p.g, p.G, p.Hq, p.B, kRowWaves / KS);
+  const RowTiling rt = make_row_tiling(p.g, p.G, p.Hq, p.B, kRowWaves / KS, /*list_blind=*/false);
   p.GS = rt.GS; p.ntile[0] = rt.ntile[0]; p.ntile[1] = rt.ntile[1];
   p.tiles_total = rt.tiles_total; p.hgroups = rt.hgroups;
   if (rt.total_wg == 0) return LOONG_OK;
@@ -324,7 +338,7 @@ int launch_bwd_dq_bf16(const loong_step_desc& d, const StepGeom& g, const void* 
   p.q_len = d.q_len; p.g = g; p.scale = d.softmax_scale; p.c = d.softmax_scale * kLog2e;
   hipStream_t st = static_cast<hipStream_t>(stream);
   // LOONG_DQ_KS (1, 2 or 4) overrides the number of key splits (tuning aid)
-  const int ks = pick_key_splits(g, p.G, p.Hq, p.B, d.head_dim, "LOONG_DQ_KS");
+  const int ks = pick_key_splits(g, p.G, p.Hq, p.B, "LOONG_DQ_KS");
   if (d.head_dim == 128) {
     if (ks == 1) return launch_cfg<128, 1>(p, st);
     if (ks == 2) return launch_cfg<128, 2>(p, st);

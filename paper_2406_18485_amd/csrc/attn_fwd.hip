@@ -180,6 +180,16 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
     kb = t < ntk0 ? 0 : 1;
     j0 = (t - (kb ? ntk0 : 0)) * TK;
   };
+  // byte offsets of this lane's pieces from the first row of a tile (full tiles only; the
+  // 32-bit form needs TK rows to span less than 4 GiB, else every tile takes the general path)
+  const bool narrow = rowbytes * TK < (int64_t(1) << 32);
+  uint32_t k_off[KI], v_off[KI];
+#pragma unroll
+  for (int i = 0; i < KI; ++i) {
+    const uint32_t ro = (uint32_t)(ld_row + i * 8 * C::RPI) * (uint32_t)rowbytes;
+    k_off[i] = ro + k_piece;
+    v_off[i] = ro + v_piece;
+  }
   auto issue_tile = [&](int t) {
     int kb, j0;
     tile_of(t, kb, j0);
@@ -188,12 +198,20 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
     const int last = len - 1 - j0;  // last valid row of the tile (>= 0); later rows repeat it
     const uint32_t kl = smem_base + (t % NBUF) * C::BUF_B + wave * 1024;
     const uint32_t vl = kl + C::TILE_B;
+    if (narrow && last >= TK - 1) {  // whole tile: uniform base in scalar registers + per-lane offset
 #pragma unroll
-    for (int i = 0; i < KI; ++i) {
-      const int r = min(ld_row + i * 8 * C::RPI, last);
-      const int64_t ro = tb + (int64_t)r * rowbytes;
-      load_to_lds_16(kbase + ro + k_piece, kl + i * 8192);
-      load_to_lds_16(vbase + ro + v_piece, vl + i * 8192);
+      for (int i = 0; i < KI; ++i) {
+        load_to_lds_16(kbase + tb, k_off[i], kl + i * 8192);
+        load_to_lds_16(vbase + tb, v_off[i], vl + i * 8192);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < KI; ++i) {
+        const int r = min(ld_row + i * 8 * C::RPI, last);
+        const int64_t ro = tb + (int64_t)r * rowbytes;
+        load_to_lds_16(kbase + ro + k_piece, kl + i * 8192);
+        load_to_lds_16(vbase + ro + v_piece, vl + i * 8192);
+      }
     }
   };
 
@@ -374,7 +392,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
 
 template <int D, int KS>
 int launch_cfg(FwdParams& p, hipStream_t st) {
-  const RowTiling rt = make_row_tiling(p.g, p.G, p.Hq, p.B, kFwdWaves / KS);
+  const RowTiling rt = make_row_tiling(p.g, p.G, p.Hq, p.B, kFwdWaves / KS, /*list_blind=*/!p.fuse);  // unfused: blind rows get the neutral result
   p.GS = rt.GS; p.ntile[0] = rt.ntile[0]; p.ntile[1] = rt.ntile[1];
   p.tiles_total = rt.tiles_total; p.hgroups = rt.hgroups;
   const int64_t total = rt.total_wg;
@@ -398,7 +416,7 @@ int launch_fwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
   p.q_len = d.q_len; p.g = g; p.c = d.softmax_scale * kLog2e; p.fuse = (d.flags & LOONG_FUSE_MERGE) ? 1 : 0;
   hipStream_t st = static_cast<hipStream_t>(stream);
   // LOONG_FWD_KS (1, 2 or 4) overrides the number of key splits (tuning aid)
-  const int ks = pick_key_splits(g, p.G, p.Hq, p.B, d.head_dim, "LOONG_FWD_KS");
+  const int ks = pick_key_splits(g, p.G, p.Hq, p.B, "LOONG_FWD_KS");
   if (d.head_dim == 128) {
     if (ks == 1) return launch_cfg<128, 1>(p, st);
     if (ks == 2) return launch_cfg<128, 2>(p, st);

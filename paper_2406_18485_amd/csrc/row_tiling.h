@@ -18,31 +18,32 @@ inline int pick_gs(int G, int nrb) {
   return 1;
 }
 
+// does q segment a see any key in this step?
+inline bool segment_sees_keys(const StepGeom& g, int a) {
+  for (int kb = 0; kb < g.nk; ++kb)
+    if (g.cls[a][kb] != LOONG_SKIP && g.k[kb].len > 0) return true;
+  return false;
+}
+
 // number of q tiles of height bmh (rows per head) that have visible keys
 inline int64_t busy_row_tiles(const StepGeom& g, int bmh) {
   int64_t n = 0;
-  for (int a = 0; a < g.nq; ++a) {
-    bool sees = false;
-    for (int kb = 0; kb < g.nk; ++kb) sees |= g.cls[a][kb] != LOONG_SKIP && g.k[kb].len > 0;
-    if (sees) n += (g.q[a].len + bmh - 1) / bmh;
-  }
+  for (int a = 0; a < g.nq; ++a)
+    if (segment_sees_keys(g, a)) n += (g.q[a].len + bmh - 1) / bmh;
   return n;
 }
 
-// Key splits: more splits give more workgroups (each streams the whole visible K/V of its
-// head through its own LDS), so splitting pays only while the chip is under-filled.  When
-// one head's K/V chunk fits an XCD's L2 the aim is a workgroup on (nearly) every CU; when
-// it does not, the extra streams cost more than the idle CUs and half the CUs is enough.
+// Key splits: more splits give more workgroups, but each workgroup streams the whole visible
+// K/V of its head through its own LDS and keeps fewer rows per staged tile, so the smallest
+// split that puts a workgroup on (nearly) every CU is taken (measured on 32K..1M-token
+// shapes: one more split than that is always slower, one fewer leaves CUs idle).
 // The environment variable named by `env` (value 1, 2 or 4) overrides the choice (tuning aid).
-inline int pick_key_splits(const StepGeom& g, int G, int Hq, int B, int head_dim, const char* env) {
+inline int pick_key_splits(const StepGeom& g, int G, int Hq, int B, const char* env) {
   if (const char* e = std::getenv(env)) {
     const int v = std::atoi(e);
     if (v == 1 || v == 2 || v == 4) return v;
   }
-  int64_t keys = 0;
-  for (int kb = 0; kb < g.nk; ++kb) keys += g.k[kb].len;
-  const int64_t kv_bytes = keys * head_dim * 2 * 2;
-  const int64_t want = kv_bytes <= (3 << 20) ? 224 : 112;
+  const int64_t want = 224;
   const int ks_opts[3] = {1, 2, 4};
   for (int i = 0; i < 3; ++i) {
     const int nrb = kRowWaves / ks_opts[i], gs = pick_gs(G, nrb);
@@ -52,18 +53,21 @@ inline int pick_key_splits(const StepGeom& g, int G, int Hq, int B, int head_dim
   return 4;
 }
 
-// Placement of the row tiles of a launch with NRB row blocks per workgroup.
+// Placement of the row tiles of a launch with NRB row blocks per workgroup.  With
+// `list_blind` false, q segments that see no key in this step get no tiles at all: the work
+// list then holds busy tiles only, and cutting it into eight equal ranges (one per XCD)
+// balances the chip.
 struct RowTiling {
   int GS, ntile[2], tiles_total, hgroups;
   int64_t total_wg;
 };
 
-inline RowTiling make_row_tiling(const StepGeom& g, int G, int Hq, int B, int nrb) {
+inline RowTiling make_row_tiling(const StepGeom& g, int G, int Hq, int B, int nrb, bool list_blind) {
   RowTiling t{};
   t.GS = pick_gs(G, nrb);
   const int bmh = 32 * nrb / t.GS;
   for (int a = 0; a < 2; ++a) {
-    t.ntile[a] = a < g.nq ? (g.q[a].len + bmh - 1) / bmh : 0;
+    t.ntile[a] = a < g.nq && (list_blind || segment_sees_keys(g, a)) ? (g.q[a].len + bmh - 1) / bmh : 0;
     t.tiles_total += t.ntile[a];
   }
   t.hgroups = Hq / t.GS;
