@@ -29,6 +29,7 @@
 
 #include "device_utils.h"
 #include "loong_internal.h"
+#include "work_map.h"
 
 namespace loong {
 namespace {
@@ -45,7 +46,7 @@ struct BwdParams {
   int add_dkv;     // 1: dk/dv are added to with atomics (accumulate flag or split iteration space)
   int nkt[2], kt_total;
   int nsplit;
-  int total_wg;
+  WorkMap map;     // units = batch x kv heads, items = key tiles x splits
 };
 
 constexpr int kBwdWaves = 4;
@@ -73,12 +74,8 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
   __shared__ __attribute__((aligned(1024))) unsigned char smem[C::SMEM_BYTES];
 
   // ---- which (batch, kv head, key tile, split)
-  const int per_xcd = gridDim.x >> 3;
-  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (logical >= p.total_wg) return;
-  const int per_head = p.kt_total * p.nsplit;
-  const int bhk = logical / per_head;
-  const int rem = logical - bhk * per_head;
+  int bhk, rem;  // key tiles in storage order see ever fewer queries: that is the ranking
+  if (!decode_work(p.map, blockIdx.x, bhk, rem)) return;
   const int kt = rem / p.nsplit, sp = rem - kt * p.nsplit;
   const int b = bhk / p.Hkv, hk = bhk - b * p.Hkv;
   const int kb = kt >= p.nkt[0] ? 1 : 0;
@@ -375,8 +372,8 @@ int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
   p.nsplit = nsplit;
   p.add_dkv = (accumulate || nsplit > 1) ? 1 : 0;
   const int64_t total = base * nsplit;
-  if (total > 0x7ffffff0) return fail(LOONG_E_UNSUPPORTED, "backward grid too large");
-  p.total_wg = (int)total;
+  if (total > 0x3ffffff0) return fail(LOONG_E_UNSUPPORTED, "backward grid too large");
+  p.map = make_work_map((int64_t)p.Hkv * p.B, (int64_t)p.kt_total * nsplit);
   if ((nsplit > 1 || unseen_keys) && !accumulate) {
     const int64_t n4 = (int64_t)p.B * p.Hkv * p.kv_len * D / 4;
     zero_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st>>>(n4, reinterpret_cast<float4*>(p.dk),
@@ -384,8 +381,7 @@ int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
     if (int rc = check_launch("loong_attn_step_bwd (clear dk/dv)")) return rc;
   }
   if (total == 0) return LOONG_OK;
-  const unsigned grid = (unsigned)((total + 7) / 8 * 8);
-  bwd_dkv_kernel<D><<<dim3(grid), dim3(kBwdWaves * 64), 0, st>>>(p);
+  bwd_dkv_kernel<D><<<dim3(p.map.grid), dim3(kBwdWaves * 64), 0, st>>>(p);
   return check_launch("loong_attn_step_bwd (bf16, dK/dV)");
 }
 

@@ -20,6 +20,7 @@
 #include "device_utils.h"
 #include "loong_internal.h"
 #include "row_tiling.h"
+#include "work_map.h"
 
 namespace loong {
 namespace {
@@ -38,7 +39,7 @@ struct DqParams {
   int ntile[2];    // q tiles per q segment
   int tiles_total;
   int hgroups;     // Hq / GS
-  int total_wg;
+  WorkMap map;     // units = batch x head groups, items = q tiles
 };
 
 template <int D, int KS>
@@ -69,13 +70,11 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
   constexpr int NDB = D / 32, NKS = D / 16, ROWB = C::ROWB, CH = C::CH;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[C::SMEM_BYTES];
 
-  // ---- which (batch, head group, q tile): consecutive logical ids sit on one XCD, and
-  // within a head group the tiles with the most visible keys come first
-  const int per_xcd = gridDim.x >> 3;
-  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (logical >= p.total_wg) return;
-  const int bh = logical / p.tiles_total;
-  const int tt = p.tiles_total - 1 - (logical - bh * p.tiles_total);
+  // ---- which (batch, head group, q tile): within a head group the tiles with the most
+  // visible keys come first
+  int bh, rank;
+  if (!decode_work(p.map, blockIdx.x, bh, rank)) return;
+  const int tt = p.tiles_total - 1 - rank;
   const int b = bh / p.hgroups, hg = bh - b * p.hgroups;
   const int qa = tt >= p.ntile[0] ? 1 : 0;
   const int tile = qa ? tt - p.ntile[0] : tt;
@@ -317,10 +316,9 @@ int launch_cfg(DqParams& p, hipStream_t st) {
   p.GS = rt.GS; p.ntile[0] = rt.ntile[0]; p.ntile[1] = rt.ntile[1];
   p.tiles_total = rt.tiles_total; p.hgroups = rt.hgroups;
   if (rt.total_wg == 0) return LOONG_OK;
-  if (rt.total_wg > 0x7ffffff0) return fail(LOONG_E_UNSUPPORTED, "backward (dQ) grid too large");
-  p.total_wg = (int)rt.total_wg;
-  const unsigned grid = (unsigned)((rt.total_wg + 7) / 8 * 8);
-  dq_kernel<D, KS><<<dim3(grid), dim3(kRowWaves * 64), 0, st>>>(p);
+  if (rt.total_wg > 0x3ffffff0) return fail(LOONG_E_UNSUPPORTED, "backward (dQ) grid too large");
+  p.map = make_work_map((int64_t)p.B * rt.hgroups, rt.tiles_total);
+  dq_kernel<D, KS><<<dim3(p.map.grid), dim3(kRowWaves * 64), 0, st>>>(p);
   return check_launch("loong_attn_step_bwd (bf16, dQ)");
 }
 

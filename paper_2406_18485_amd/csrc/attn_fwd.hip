@@ -30,6 +30,7 @@
 #include "device_utils.h"
 #include "loong_internal.h"
 #include "row_tiling.h"
+#include "work_map.h"
 
 namespace loong {
 namespace {
@@ -51,7 +52,7 @@ struct FwdParams {
   int ntile[2];    // q tiles per q segment
   int tiles_total;
   int hgroups;     // Hq / GS
-  int total_wg;
+  WorkMap map;     // units = batch x head groups, items = q tiles
 };
 
 template <int D, int KS>
@@ -83,13 +84,11 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
   constexpr int NJB = BNS / 32, NDB = D / 32, NKS = D / 16, ROWB = C::ROWB, CH = C::CH, RP = C::RP;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[C::SMEM_BYTES];
 
-  // ---- which (batch, head group, q tile): consecutive logical ids sit on one XCD, and
-  // within a head group the tiles with the most visible keys come first
-  const int per_xcd = gridDim.x >> 3;
-  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (logical >= p.total_wg) return;
-  const int bh = logical / p.tiles_total;
-  const int tt = p.tiles_total - 1 - (logical - bh * p.tiles_total);
+  // ---- which (batch, head group, q tile): within a head group the tiles with the most
+  // visible keys come first
+  int bh, rank;
+  if (!decode_work(p.map, blockIdx.x, bh, rank)) return;
+  const int tt = p.tiles_total - 1 - rank;
   const int b = bh / p.hgroups, hg = bh - b * p.hgroups;
   const int qa = tt >= p.ntile[0] ? 1 : 0;
   const int tile = qa ? tt - p.ntile[0] : tt;
@@ -397,10 +396,9 @@ int launch_cfg(FwdParams& p, hipStream_t st) {
   p.tiles_total = rt.tiles_total; p.hgroups = rt.hgroups;
   const int64_t total = rt.total_wg;
   if (total == 0) return LOONG_OK;
-  if (total > 0x7ffffff0) return fail(LOONG_E_UNSUPPORTED, "forward grid too large");
-  p.total_wg = (int)total;
-  const unsigned grid = (unsigned)((total + 7) / 8 * 8);
-  fwd_kernel<D, KS><<<dim3(grid), dim3(kFwdWaves * 64), 0, st>>>(p);
+  if (total > 0x3ffffff0) return fail(LOONG_E_UNSUPPORTED, "forward grid too large");
+  p.map = make_work_map((int64_t)p.B * rt.hgroups, rt.tiles_total);
+  fwd_kernel<D, KS><<<dim3(p.map.grid), dim3(kFwdWaves * 64), 0, st>>>(p);
   return check_launch("loong_attn_step_fwd (bf16)");
 }
 

@@ -43,7 +43,12 @@ inline int pick_key_splits(const StepGeom& g, int G, int Hq, int B, const char* 
     const int v = std::atoi(e);
     if (v == 1 || v == 2 || v == 4) return v;
   }
-  const int64_t want = 224;
+  // a step with a diagonal block has tiles of very different length: two workgroups per CU,
+  // longest first, even them out
+  bool diag = false;
+  for (int a = 0; a < g.nq; ++a)
+    for (int kb = 0; kb < g.nk; ++kb) diag |= g.cls[a][kb] == LOONG_DIAG;
+  const int64_t want = diag ? 448 : 224;
   const int ks_opts[3] = {1, 2, 4};
   for (int i = 0; i < 3; ++i) {
     const int nrb = kRowWaves / ks_opts[i], gs = pick_gs(G, nrb);
