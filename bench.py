@@ -36,6 +36,11 @@ def pairs_per_head(cfg) -> int:
     return L * (L + 1) // 2 + (cfg.cp - 1) * (L * L // 2)
 
 
+def auto_cpu_rows(cfg) -> int:
+    """Rows of the oracle sample for about 15 s of host work (the oracle does ~8e7 (row, key) pairs per second)."""
+    return int(max(64, min(cfg.L, 1.2e9 / (cfg.hq * cfg.S))))
+
+
 def cpu_baseline(cfg, inp, budget_rows: int):
     """Time the oracle as it stands (numpy fp64, its BLAS threads) on a row sample."""
     import numpy as np
@@ -65,7 +70,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1, help="index into workloads.CONFIGS (1 = 7B MHA shard, 32K)")
-    ap.add_argument("--cpu-rows", type=int, default=512, help="rows of the oracle sample (0: skip the CPU baseline)")
+    ap.add_argument("--cpu-rows", type=int, default=-1,
+                    help="rows of the oracle sample (0: skip the CPU baseline; -1: sized for about 15 s of host work)")
     ap.add_argument("--unfused", action="store_true", help="run Attention and Update as separate kernels")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="launch only device-to-device copies of 256 MiB (reference for the HBM byte counters) and exit")
@@ -156,6 +162,40 @@ def main():
         "dq_kernel": {"flop_per_pair": "6*d (S and dP recomputed)", "avg_launch_ms": round(dq_ms / cfg.cp, 4),
                       "tflops": round(6.0 * cfg.d * pairs / (dq_ms * 1e-3) / 1e12, 1)},
     }
+    # ---- extra figures, measured after the timed region ------------------------------------
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    # per step class (rank 0: step 0 holds the own chunk = the diagonal step, the others two FULL blocks)
+    def cls_ms(sel):
+        idx = [i for i, st in enumerate(rep.plan) if sel(st)]
+        if not idx:
+            return None
+        tot = sum(e["bwd"][i][0].elapsed_time(e["bwd"][i][2]) for e in events for i in idx)
+        return round(tot / (len(idx) * args.steps), 4)
+    step_classes = {"bwd_ms_diagonal_step": cls_ms(lambda st: st["src_rank"] == cfg.rank),
+                    "bwd_ms_other_steps": cls_ms(lambda st: st["src_rank"] != cfg.rank)}
+    # Update as a kernel of its own (HBM-bound): 3 x 4 x d + 3 x 4 bytes per merged row
+    rows = cfg.hq * cfg.L
+    blk_out, blk_lse = torch.randn(rows, cfg.d, device="cuda:0"), torch.randn(rows, device="cuda:0")
+    run_out, run_lse = torch.randn(rows, cfg.d, device="cuda:0"), torch.randn(rows, device="cuda:0")
+    merge_ms = timed(lambda: P.lse_merge(rows, cfg.d, run_out, run_lse, blk_out, blk_lse), 20)
+    merge = {"rows": rows, "ms": round(merge_ms, 4), "bytes_per_row": 12 * cfg.d + 12,
+             "GB_per_s": round(rows * (12 * cfg.d + 12) / (merge_ms * 1e-3) / 1e9, 1), "hbm_peak_GB_per_s": 8000}
+    # the matrix cores alone, at the clocks the chip really holds
+    wgs, iters_probe = 256 * 8, 4000
+    sink = torch.empty(wgs * 256, device="cuda:0")
+    probe_ms = timed(lambda: P.mfma_probe(wgs, iters_probe, sink), 3)
+    mfma_sustained = wgs * 4 * iters_probe * 4 * 32768 / (probe_ms * 1e-3) / 1e12
+
     result = {
         "metric": "fwd+bwd ring-step attention TFLOP/s on 1 GPU; % of bf16 MFMA peak",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -173,10 +213,15 @@ def main():
                      "avg_launch_ms": round(dkv_ms / cfg.cp, 4), "launches_per_step": cfg.cp,
                      "flop_per_launch": round(8.0 * cfg.d * pairs / cfg.cp)},
         "kernels": per_kernel,
+        "step_classes": step_classes,
+        "merge_only": merge,
+        "mfma_only_probe_tflops": round(mfma_sustained, 1),
+        "pct_of_mfma_only_probe": round(100.0 * tflops / mfma_sustained, 2),
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
     }
-    if args.cpu_rows > 0:
-        result["cpu_baseline"] = cpu_baseline(cfg, inp, args.cpu_rows)
+    cpu_rows = auto_cpu_rows(cfg) if args.cpu_rows < 0 else args.cpu_rows
+    if cpu_rows > 0:
+        result["cpu_baseline"] = cpu_baseline(cfg, inp, cpu_rows)
     print(json.dumps(result), flush=True)
 
 

@@ -157,6 +157,16 @@ LOONG_API int loong_validate_step(const loong_step_desc* desc);
 /* Text of the calling thread's last error ("" if none). Never NULL. */
 LOONG_API const char* loong_last_error(void);
 
+/*
+ * Measurement aid: a kernel of nothing but dependent-free v_mfma_f32_32x32x16_bf16 chains on
+ * every SIMD of the device (`workgroups` x 4 waves x `iters` x 4 instructions).  It writes
+ * one float per thread to `sink` (workgroups * 256 floats, device memory) so that the work
+ * cannot be dropped.  Timing it gives the matrix-core rate the chip sustains at its real
+ * clocks, the second ceiling `bench.py` prints beside the published peak.  FLOPs of a call:
+ * workgroups * 4 * iters * 4 * 32768.  Errors: LOONG_E_NULL, LOONG_E_SHAPE (non-positive sizes).
+ */
+LOONG_API int loong_mfma_probe(int32_t workgroups, int32_t iters, float* sink, void* stream);
+
 /* Library version, major*10000 + minor*100 + patch. */
 LOONG_API int loong_version(void);
 

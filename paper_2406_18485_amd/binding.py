@@ -20,7 +20,7 @@ FUSE_MERGE, ACCUM_DKV, COMPUTE_DELTA, BWD_ONLY_DKV, BWD_ONLY_DQ = 1, 2, 4, 8, 16
 EXPORTS = (
     "loong_zigzag_mask", "loong_attn_step_fwd", "loong_lse_merge", "loong_attn_step_bwd",
     "loong_bwd_delta", "loong_init_running", "loong_finalize_out", "loong_validate_step",
-    "loong_last_error", "loong_version",
+    "loong_last_error", "loong_version", "loong_mfma_probe",
 )
 
 
@@ -58,6 +58,7 @@ lib.loong_bwd_delta.argtypes = [C.POINTER(StepDesc), _vp, _vp, _vp, _vp]
 lib.loong_init_running.argtypes = [_i64, _i32, _vp, _vp, _vp]
 lib.loong_finalize_out.argtypes = [_i64, _i32, _vp, _vp, _i32, _vp]
 lib.loong_validate_step.argtypes = [C.POINTER(StepDesc)]
+lib.loong_mfma_probe.argtypes = [_i32, _i32, _vp, _vp]
 lib.loong_last_error.restype = C.c_char_p
 for _n in EXPORTS:
     if _n != "loong_last_error":
@@ -93,6 +94,10 @@ def last_error() -> str:
 
 def version() -> int:
     return lib.loong_version()
+
+
+def mfma_probe(workgroups: int, iters: int, sink, stream=None):
+    _check(lib.loong_mfma_probe(workgroups, iters, _ptr(sink), _stream(stream)))
 
 
 def make_desc(*, batch, n_q_heads, n_kv_heads, head_dim, q_len, kv_len, dtype, softmax_scale,

@@ -229,3 +229,33 @@ int loong_bwd_delta(const loong_step_desc* desc, const void* o, const void* d_o,
 }
 
 }  // extern "C"
+
+// ---- measurement aid: matrix cores only ---------------------------------------------------
+namespace loong {
+namespace {
+__global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float* sink) {
+  const int lane = threadIdx.x & 63;
+  // operands that keep the accumulators finite and differ per lane
+  const bf16x8_t a = as_bf16x8(make_uint4(0x3c003c00u + lane, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u));
+  const bf16x8_t b = as_bf16x8(make_uint4(0x38003800u, 0x38003800u + lane, 0x38003800u, 0x38003800u));
+  floatx16_t c[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) c[i][v] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c[i] = mfma32(a, b, c[i]);
+  }
+  sink[blockIdx.x * 256 + threadIdx.x] = c[0][0] + c[1][5] + c[2][10] + c[3][15];
+}
+}  // namespace
+}  // namespace loong
+
+extern "C" int loong_mfma_probe(int32_t workgroups, int32_t iters, float* sink, void* stream) {
+  loong::clear_error();
+  if (!sink) return loong::fail(LOONG_E_NULL, "loong_mfma_probe: NULL sink");
+  if (workgroups <= 0 || iters <= 0) return loong::fail(LOONG_E_SHAPE, "loong_mfma_probe: sizes must be positive");
+  loong::mfma_probe_kernel<<<dim3((unsigned)workgroups), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(iters, sink);
+  return loong::check_launch("loong_mfma_probe");
+}
