@@ -72,7 +72,7 @@ struct FwdCfg {
   static constexpr int KI = TILE_B / 1024 / kFwdWaves;  // loads per wave per K (or V) tile
   static constexpr int SLOT_F4 = (D / 32) * 4 + 1; // float4 per lane of one wave's partial result
   static constexpr int TILE_BYTES = NBUF * BUF_B;
-  static constexpr int COMB_BYTES = (KS - 1) * NRB * SLOT_F4 * 64 * 16;
+  static constexpr int COMB_BYTES = (KS > 1 ? KS : 0) * NRB * SLOT_F4 * 64 * 16;
   static constexpr int SMEM_BYTES = TILE_BYTES > COMB_BYTES ? TILE_BYTES : COMB_BYTES;
   static_assert(KI >= 1 && KI * 1024 * kFwdWaves == TILE_B, "tile must split evenly over the waves");
 };
@@ -131,37 +131,6 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
       if (hh == 0) *lse_ptr = -INFINITY;
     }
     return;
-  }
-
-  // ---- Q fragments (B operand of S^T = K Q^T): row my_row, columns 16*ks + 8*hh .. +7
-  bf16x8_t qf[NKS];
-  {
-    const uint16_t* qrow = p.q + b * p.qs[0] + h * p.qs[1] + (int64_t)my_row * p.qs[2];
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) qf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(qrow + ks * 16 + hh * 8));
-  }
-
-  // ---- running state: maximum (log2 units), partial row sum of this half, O^T accumulators.
-  // Only split 0 starts from the running result.
-  float m_run = -INFINITY, l_run = 0.f;
-  floatx16_t o[NDB];
-#pragma unroll
-  for (int db = 0; db < NDB; ++db)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-  if (p.fuse && ksp == 0) {
-    const float prev = *lse_ptr;
-    if (prev != -INFINITY) {
-      m_run = prev * kLog2e;
-      l_run = hh == 0 ? 1.f : 0.f;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          const float4 x = *reinterpret_cast<const float4*>(out_row + db * 32 + 8 * vq + 4 * hh);
-          o[db][4 * vq + 0] = x.x; o[db][4 * vq + 1] = x.y; o[db][4 * vq + 2] = x.z; o[db][4 * vq + 3] = x.w;
-        }
-    }
   }
 
   // ---- staging: global -> LDS directly.  Load i of this wave fills LDS bytes
@@ -245,13 +214,52 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
     return wave_live && j0 < klen && !(isdiag && j0 > wrow0 + 31);
   };
 
-  // ---- pipeline: PD tiles in flight.  Everything loaded so far (Q, running state) is waited
-  // for here, so that no counter wait of the compiler's own ends up inside the loop, where it
-  // would also wait for the tiles in flight.
-  wait_vmcnt<0>();
+  // ---- pipeline: PD tiles in flight.  The first tiles are requested before the Q fragments
+  // and the running state, so that the three latencies overlap; everything is then waited
+  // for before the loop, so that no counter wait of the compiler's own ends up inside it,
+  // where it would also wait for the tiles in flight.
 #pragma unroll
   for (int t = 0; t < PD; ++t)
     if (t < total_t) issue_tile(t);
+
+  // ---- Q fragments (B operand of S^T = K Q^T): row my_row, columns 16*ks + 8*hh .. +7
+  bf16x8_t qf[NKS];
+  {
+    const uint16_t* qrow = p.q + b * p.qs[0] + h * p.qs[1] + (int64_t)my_row * p.qs[2];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(qrow + ks * 16 + hh * 8));
+  }
+
+  // ---- running state: maximum (log2 units), partial row sum of this half, O^T accumulators.
+  // Only split 0 starts from the running result; its rows of `out` are requested together
+  // with the LSE (one round trip to memory, not two) and dropped if the LSE says "empty".
+  float m_run = -INFINITY, l_run = 0.f;
+  floatx16_t o[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+  if (p.fuse && ksp == 0) {
+    const float prev = *lse_ptr;
+    float4 x[NDB][4];
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) x[db][vq] = *reinterpret_cast<const float4*>(out_row + db * 32 + 8 * vq + 4 * hh);
+    if (prev != -INFINITY) {
+      m_run = prev * kLog2e;
+      l_run = hh == 0 ? 1.f : 0.f;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          o[db][4 * vq + 0] = x[db][vq].x; o[db][4 * vq + 1] = x[db][vq].y;
+          o[db][4 * vq + 2] = x[db][vq].z; o[db][4 * vq + 3] = x[db][vq].w;
+        }
+    }
+  }
+
+  wait_vmcnt<0>();
 
   for (int t = 0; t < total_t; ++t) {
     // this wave's loads of tile t have landed when at most the later tiles' are outstanding
@@ -338,12 +346,14 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
         }
   }
 
-  // ---- combine the key splits: splits 1.. park (m, l, O^T) in LDS, split 0 folds them in
+  // ---- combine the key splits through LDS: every split parks (m, l, O^T); split j then
+  // folds column block j (32 columns) of all splits, so the four waves share the work
+  // (with fewer column blocks than splits the surplus waves leave).
   if (KS > 1) {
     __syncthreads();  // all reads of the last tile are done: the tile buffers are reused
     float4* slots = reinterpret_cast<float4*>(smem);
-    if (ksp > 0) {
-      float4* mine = slots + ((ksp - 1) * NRB + rb) * C::SLOT_F4 * 64 + lane;
+    {
+      float4* mine = slots + (ksp * NRB + rb) * C::SLOT_F4 * 64 + lane;
 #pragma unroll
       for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -352,27 +362,47 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
       mine[(NDB * 4) * 64] = make_float4(m_run, l_run, 0.f, 0.f);
     }
     __syncthreads();
-    if (ksp > 0) return;
-#pragma unroll 1
-    for (int sp = 1; sp < KS; ++sp) {
-      const float4* theirs = slots + ((sp - 1) * NRB + rb) * C::SLOT_F4 * 64 + lane;
-      const float4 st = theirs[(NDB * 4) * 64];
-      const float m_new = fmaxf(m_run, st.x);
-      const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-      const float wa = fast_exp2(m_run - m_ref), wb = fast_exp2(st.x - m_ref);  // exp2(-inf) = 0
-      l_run = l_run * wa + st.y * wb;
+    constexpr int DBW = (NDB + KS - 1) / KS;  // column blocks per wave
+    const int db0 = ksp * DBW;
+    if (db0 >= NDB) return;
+    // common maximum and the weights of the splits (fixed order: bit-reproducible)
+    float m_all = -INFINITY;
+    float ms[KS], ls[KS];
 #pragma unroll
-      for (int db = 0; db < NDB; ++db)
+    for (int sp = 0; sp < KS; ++sp) {
+      const float4 st = slots[((sp * NRB + rb) * C::SLOT_F4 + NDB * 4) * 64 + lane];
+      ms[sp] = st.x; ls[sp] = st.y;
+      m_all = fmaxf(m_all, st.x);
+    }
+    const float m_ref = m_all == -INFINITY ? 0.f : m_all;
+    float l_all = 0.f, w[KS];
+#pragma unroll
+    for (int sp = 0; sp < KS; ++sp) {
+      w[sp] = fast_exp2(ms[sp] - m_ref);  // exp2(-inf) = 0
+      l_all += ls[sp] * w[sp];
+    }
+    const float l_tot = l_all + other_half(l_all);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    if (row_ok) {
+#pragma unroll
+      for (int d2 = 0; d2 < DBW; ++d2) {
+        const int db = db0 + d2;
+        if (db >= NDB) break;
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
-          const float4 x = theirs[(db * 4 + vq) * 64];
-          o[db][4 * vq + 0] = o[db][4 * vq + 0] * wa + x.x * wb;
-          o[db][4 * vq + 1] = o[db][4 * vq + 1] * wa + x.y * wb;
-          o[db][4 * vq + 2] = o[db][4 * vq + 2] * wa + x.z * wb;
-          o[db][4 * vq + 3] = o[db][4 * vq + 3] * wa + x.w * wb;
+          float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+          for (int sp = 0; sp < KS; ++sp) {
+            const float4 xv = slots[((sp * NRB + rb) * C::SLOT_F4 + db * 4 + vq) * 64 + lane];
+            acc.x += xv.x * w[sp]; acc.y += xv.y * w[sp]; acc.z += xv.z * w[sp]; acc.w += xv.w * w[sp];
+          }
+          *reinterpret_cast<float4*>(out_row + db * 32 + 8 * vq + 4 * hh) =
+              make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
         }
-      m_run = m_new;
+      }
+      if (ksp == 0 && hh == 0) *lse_ptr = l_tot > 0.f ? (m_all + fast_log2(l_tot)) * kLn2 : -INFINITY;
     }
+    return;
   }
 
   // ---- normalise and store
