@@ -1,0 +1,106 @@
+"""The performance model (Sec. "Performance Analysis"): oracle pins, then the C calculator against the oracle."""
+import ctypes as C
+import itertools
+import math
+
+import pytest
+
+from oracle import cost_model_oracle as cm
+
+MIB = 1 << 20
+LLAMA7B = dict(S=131072, D=4096, H=32)
+
+
+# ------------------------------------------------------------------ pins of the oracle
+def test_worked_size_from_the_paper():
+    # Sec. "Inefficient Performance" (motivation): GQA, 128K tokens, 8 GPUs in one ring -> 64 MB per step
+    assert cm.size_kv(131072, 4096, 32, 8, d_hp=1, d_cp=8) == 64 * MIB
+
+
+def test_size_kv_depends_on_d_sp_only_without_replication():
+    a = cm.size_kv(1 << 20, 4096, 32, 32, d_hp=8, d_cp=8)
+    b = cm.size_kv(1 << 20, 4096, 32, 32, d_hp=2, d_cp=32)
+    assert a == b == 4.0 * (1 << 20) * 4096 / 64
+
+
+def test_gqa_equals_mha_traffic_when_every_head_has_its_own_gpu():
+    assert cm.size_kv(65536, 4096, 32, 8, d_hp=32, d_cp=2) == cm.size_kv(65536, 4096, 32, 32, d_hp=32, d_cp=2)
+    assert cm.size_kv(65536, 4096, 32, 8, d_hp=4, d_cp=16) == 0.25 * cm.size_kv(65536, 4096, 32, 32, d_hp=4, d_cp=16)
+
+
+def test_alltoall_volume_limits():
+    assert cm.alltoall_volume(65536, 4096, 32, 32, d_hp=1, d_cp=64) == 0.0
+    # MHA: q, k, v, out are four equal chunks of 2SD/d_sp bytes
+    v = cm.alltoall_volume(65536, 4096, 32, 32, d_hp=8, d_cp=8)
+    assert math.isclose(v, 4 * (2 * 65536 * 4096 / 64) * 7 / 8)
+
+
+def test_compute_time_scaling():
+    t = cm.t_comp_fwd(1e-18, 131072, 4096, d_hp=4, d_cp=8)
+    assert math.isclose(t, 1e-18 * 131072 ** 2 * 4096 / (8 * 32))
+    assert math.isclose(cm.t_comp_bwd(1e-18, 131072, 4096, 4, 8), 3 * t)
+    # total forward compute of a layer, d_cp micro-steps, does not depend on the split of d_sp into rings
+    assert math.isclose(8 * cm.t_comp_fwd(1e-18, 131072, 4096, 4, 8) * 4, 1e-18 * 131072 ** 2 * 4096 / 8)
+
+
+def test_inner_ring_limits():
+    assert cm.t_inner_ring(5.0, 1.0, 2.0, w=4) == 20.0           # compute hides everything
+    assert cm.t_inner_ring(1.0, 5.0, 7.0, w=4) == 3 * 5.0 + 7.0   # communication bound
+    assert cm.t_inner_ring(3.0, 1.0, 9.0, w=1) == 9.0             # a ring of one: only the outer transfer
+
+
+def test_objective_reduces_to_compute_when_links_are_infinitely_fast():
+    t = cm.objective(1e-18, 131072, 4096, 32, 8, d_hp=4, d_cp=8, w=4, bw_inner=1e30, bw_outer=1e30, bw_alltoall=1e30)
+    assert math.isclose(t, 8 * 4 * cm.t_comp_fwd(1e-18, 131072, 4096, 4, 8))
+
+
+# ------------------------------------------------------------------ the C calculator against the oracle
+@pytest.fixture(scope="module")
+def P():
+    import paper_2406_18485_amd as P
+    return P
+
+
+GRID = [dict(S=S, D=4096, H=32, H_kv=hkv, d_hp=hp, d_cp=cp, w=w)
+        for S, hkv, (hp, cp), w in itertools.product((131072, 1 << 20), (8, 32), ((1, 8), (4, 16), (8, 8), (32, 2)), (1, 2, 4, 8))
+        if cp % w == 0]
+
+
+@pytest.mark.parametrize("g", GRID)
+def test_calculator_matches_the_oracle(P, g):
+    link = dict(alpha_fwd=2.5e-19, bw_p2p_inner=4.0e11, bw_p2p_outer=5.0e10, bw_alltoall=2.0e11, latency=1.5e-5)
+    out = P.cost_model(**g, **link)
+    kv = cm.size_kv(g["S"], g["D"], g["H"], g["H_kv"], g["d_hp"], g["d_cp"])
+    assert out["size_kv"] == kv
+    assert out["size_q"] == cm.size_q(g["S"], g["D"], g["d_hp"], g["d_cp"])
+    assert math.isclose(out["alltoall_volume"], cm.alltoall_volume(g["S"], g["D"], g["H"], g["H_kv"], g["d_hp"], g["d_cp"]), rel_tol=1e-12)
+    tf = cm.t_comp_fwd(link["alpha_fwd"], g["S"], g["D"], g["d_hp"], g["d_cp"])
+    assert math.isclose(out["t_comp_fwd"], tf, rel_tol=1e-12) and math.isclose(out["t_comp_bwd"], 3 * tf, rel_tol=1e-12)
+    fwd = cm.t_inner_ring(tf, link["latency"] + kv / link["bw_p2p_inner"], link["latency"] + kv / link["bw_p2p_outer"], g["w"])
+    assert math.isclose(out["t_inner_ring_fwd"], fwd, rel_tol=1e-12)
+    want = cm.objective(link["alpha_fwd"], g["S"], g["D"], g["H"], g["H_kv"], g["d_hp"], g["d_cp"], g["w"],
+                        link["bw_p2p_inner"], link["bw_p2p_outer"], link["bw_alltoall"], link["latency"])
+    assert math.isclose(out["objective"], want, rel_tol=1e-12)
+
+
+def test_calculator_rejects_bad_grids(P):
+    base = dict(S=131072, D=4096, H=32, H_kv=8, alpha_fwd=1e-19, bw_p2p_inner=1e11, bw_p2p_outer=1e10, bw_alltoall=1e11)
+    for bad in (dict(d_hp=3, d_cp=8, w=4), dict(d_hp=64, d_cp=2, w=1), dict(d_hp=4, d_cp=8, w=3), dict(d_hp=4, d_cp=0, w=1)):
+        with pytest.raises(P.LoongError):
+            P.cost_model(**base, **bad)
+    with pytest.raises(P.LoongError):
+        P.cost_model(**dict(base, bw_p2p_inner=0.0), d_hp=4, d_cp=8, w=4)
+
+
+def test_search_returns_the_minimum_over_the_grid(P):
+    link = dict(alpha_fwd=2.5e-19, bw_p2p_inner=4.0e11, bw_p2p_outer=5.0e10, bw_alltoall=2.0e11, latency=1.5e-5)
+    best = P.cost_search(S=1 << 20, D=4096, H=32, H_kv=8, d_sp=64, max_w=8, **link)
+    cands = []
+    for hp in (1, 2, 4, 8, 16, 32):
+        cp = 64 // hp
+        for w in (1, 2, 4, 8):
+            if cp % w == 0:
+                cands.append((cm.objective(link["alpha_fwd"], 1 << 20, 4096, 32, 8, hp, cp, w, link["bw_p2p_inner"],
+                                           link["bw_p2p_outer"], link["bw_alltoall"], link["latency"]), hp, cp, w))
+    t, hp, cp, w = min(cands)
+    assert (best["d_hp"], best["d_cp"], best["w"]) == (hp, cp, w) and math.isclose(best["objective"], t, rel_tol=1e-12)
