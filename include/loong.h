@@ -158,6 +158,52 @@ LOONG_API int loong_validate_step(const loong_step_desc* desc);
 LOONG_API const char* loong_last_error(void);
 
 /*
+ * Performance model of 2D-Attention (paper: Sec. "Performance Analysis": "Computation
+ * Analysis", "P2P Communication Analysis", "SeqAlltoAll Communication Analysis").  Host only.
+ * Inputs: sequence length S and hidden size D (elements), H query heads, H_kv key/value
+ * heads, the grid d_hp x d_cp, the inner ring size w (divides d_cp; d_hp divides H), the
+ * forward compute constant alpha_fwd in seconds per unit of S^2 D (fit it to a measured
+ * forward micro-step), the bandwidths in bytes per second of an inner-ring transfer, an
+ * outer-ring transfer and the all-to-all, and a per-message latency in seconds.
+ * Outputs, in the paper's notation (bytes and seconds):
+ *   size_kv = max(H_kv, d_hp) / H * 4 S D / d_sp        size_q = 2 S D / d_sp
+ *   alltoall_volume = sum over q, k, v, out of Size(i) * (d_hp - 1) / d_hp   (one phase)
+ *   t_comp_fwd = alpha S^2 D / (d_cp d_sp)               t_comp_bwd = 3 t_comp_fwd
+ *   t_p2p_* = latency + bytes / bandwidth; the backward moves the chunk and its gradient (2x)
+ *   t_inner_ring = A (w - 1) + B,  A = max(t_comp, t_p2p_inner),  B = max(t_comp, t_p2p_outer)
+ *   t_seq_alltoall = 2 * alltoall_volume / bw_alltoall   (forward and backward phase)
+ *   objective = t_seq_alltoall + (t_inner_ring_fwd + t_inner_ring_bwd) * d_cp / w
+ * Errors: LOONG_E_NULL; LOONG_E_SHAPE for non-positive sizes, bandwidths or alpha, d_hp not
+ * dividing H, w not dividing d_cp, H_kv not dividing H.
+ */
+typedef struct loong_cost_in {
+  double S, D;
+  int32_t H, H_kv, d_hp, d_cp, w;
+  double alpha_fwd;
+  double bw_p2p_inner, bw_p2p_outer, bw_alltoall;
+  double latency;
+} loong_cost_in;
+
+typedef struct loong_cost_out {
+  double size_kv, size_q, alltoall_volume;
+  double t_comp_fwd, t_comp_bwd;
+  double t_p2p_inner_fwd, t_p2p_outer_fwd, t_p2p_inner_bwd, t_p2p_outer_bwd;
+  double t_inner_ring_fwd, t_inner_ring_bwd, t_seq_alltoall, objective;
+} loong_cost_out;
+
+LOONG_API int loong_cost_model(const loong_cost_in* in, loong_cost_out* out);
+
+/*
+ * The grid with the smallest objective for d_sp GPUs: every d_hp that divides both d_sp and H,
+ * d_cp = d_sp / d_hp, every w <= max_w that divides d_cp (ties: smaller d_hp, then smaller w).
+ * `in->d_hp`, `in->d_cp`, `in->w` are ignored; the winner is written to `best_in` (the full
+ * input with its grid) and `best_out`.  Errors as loong_cost_model, plus LOONG_E_SHAPE when no
+ * grid is admissible.
+ */
+LOONG_API int loong_cost_search(const loong_cost_in* in, int32_t d_sp, int32_t max_w, loong_cost_in* best_in,
+                                loong_cost_out* best_out);
+
+/*
  * Measurement aid: a kernel of nothing but dependent-free v_mfma_f32_32x32x16_bf16 chains on
  * every SIMD of the device (`workgroups` x 4 waves x `iters` x 4 instructions).  It writes
  * one float per thread to `sink` (workgroups * 256 floats, device memory) so that the work

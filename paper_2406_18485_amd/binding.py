@@ -20,7 +20,7 @@ FUSE_MERGE, ACCUM_DKV, COMPUTE_DELTA, BWD_ONLY_DKV, BWD_ONLY_DQ = 1, 2, 4, 8, 16
 EXPORTS = (
     "loong_zigzag_mask", "loong_attn_step_fwd", "loong_lse_merge", "loong_attn_step_bwd",
     "loong_bwd_delta", "loong_init_running", "loong_finalize_out", "loong_validate_step",
-    "loong_last_error", "loong_version", "loong_mfma_probe",
+    "loong_last_error", "loong_version", "loong_mfma_probe", "loong_cost_model", "loong_cost_search",
 )
 
 
@@ -41,6 +41,20 @@ class StepDesc(C.Structure):
     ]
 
 
+class CostIn(C.Structure):
+    """Mirror of loong_cost_in."""
+    _fields_ = [("S", C.c_double), ("D", C.c_double), ("H", C.c_int32), ("H_kv", C.c_int32), ("d_hp", C.c_int32),
+                ("d_cp", C.c_int32), ("w", C.c_int32), ("alpha_fwd", C.c_double), ("bw_p2p_inner", C.c_double),
+                ("bw_p2p_outer", C.c_double), ("bw_alltoall", C.c_double), ("latency", C.c_double)]
+
+
+class CostOut(C.Structure):
+    """Mirror of loong_cost_out."""
+    _fields_ = [(n, C.c_double) for n in (
+        "size_kv", "size_q", "alltoall_volume", "t_comp_fwd", "t_comp_bwd", "t_p2p_inner_fwd", "t_p2p_outer_fwd",
+        "t_p2p_inner_bwd", "t_p2p_outer_bwd", "t_inner_ring_fwd", "t_inner_ring_bwd", "t_seq_alltoall", "objective")]
+
+
 if not os.path.exists(LIB_PATH):
     raise ImportError(
         f"{LIB_PATH} is missing: build it with `python -m paper_2406_18485_amd.build` "
@@ -59,6 +73,8 @@ lib.loong_init_running.argtypes = [_i64, _i32, _vp, _vp, _vp]
 lib.loong_finalize_out.argtypes = [_i64, _i32, _vp, _vp, _i32, _vp]
 lib.loong_validate_step.argtypes = [C.POINTER(StepDesc)]
 lib.loong_mfma_probe.argtypes = [_i32, _i32, _vp, _vp]
+lib.loong_cost_model.argtypes = [C.POINTER(CostIn), C.POINTER(CostOut)]
+lib.loong_cost_search.argtypes = [C.POINTER(CostIn), _i32, _i32, C.POINTER(CostIn), C.POINTER(CostOut)]
 lib.loong_last_error.restype = C.c_char_p
 for _n in EXPORTS:
     if _n != "loong_last_error":
@@ -94,6 +110,31 @@ def last_error() -> str:
 
 def version() -> int:
     return lib.loong_version()
+
+
+def _cost_in(S, D, H, H_kv, alpha_fwd, bw_p2p_inner, bw_p2p_outer, bw_alltoall, latency=0.0, d_hp=1, d_cp=1, w=1):
+    return CostIn(S=S, D=D, H=H, H_kv=H_kv, d_hp=d_hp, d_cp=d_cp, w=w, alpha_fwd=alpha_fwd, bw_p2p_inner=bw_p2p_inner,
+                  bw_p2p_outer=bw_p2p_outer, bw_alltoall=bw_alltoall, latency=latency)
+
+
+def _as_dict(st) -> dict:
+    return {n: getattr(st, n) for n, _ in st._fields_}
+
+
+def cost_model(**kw) -> dict:
+    """loong_cost_model: keyword arguments are the fields of loong_cost_in; returns loong_cost_out as a dict."""
+    out = CostOut()
+    _check(lib.loong_cost_model(C.byref(_cost_in(**kw)), C.byref(out)))
+    return _as_dict(out)
+
+
+def cost_search(d_sp: int, max_w: int, **kw) -> dict:
+    """loong_cost_search: the best grid for d_sp GPUs; returns the outputs plus d_hp, d_cp, w."""
+    best_in, best_out = CostIn(), CostOut()
+    _check(lib.loong_cost_search(C.byref(_cost_in(**kw)), d_sp, max_w, C.byref(best_in), C.byref(best_out)))
+    res = _as_dict(best_out)
+    res.update(d_hp=best_in.d_hp, d_cp=best_in.d_cp, w=best_in.w)
+    return res
 
 
 def mfma_probe(workgroups: int, iters: int, sink, stream=None):
