@@ -158,6 +158,34 @@ LOONG_API int loong_validate_step(const loong_step_desc* desc);
 LOONG_API const char* loong_last_error(void);
 
 /*
+ * Row permutation: the local half of SeqAlltoAll and the KV replication of Alg. 1 (paper:
+ * Sec. 3.1 steps 1 and 3; Sec. "KV Replication for GQA").  Copies n0*n1*n2 rows of
+ * `row_bytes` bytes (a multiple of 16; rows 16-byte aligned): row (a, b, c) is read at
+ * in + (a*in_stride[0] + b*in_stride[1] + c*in_stride[2]) bytes and written at the same
+ * expression with out_stride.  Strides are in BYTES, multiples of 16; an input stride may be 0
+ * (replication), output rows must not overlap.  Examples, with e = element size and
+ * hl = H / d_hp:
+ *   heads of (s, H, d) token-major into d_hp messages (d_hp, hl, s, d):
+ *     n = {d_hp, hl, s}, in_stride = {hl*d*e, d*e, H*d*e}, out_stride = {hl*s*d*e, s*d*e, d*e}
+ *   d_hp received messages (d_hp, hl, s, d) into (hl, d_hp*s, d):
+ *     n = {d_hp, hl, s}, in_stride = {hl*s*d*e, s*d*e, d*e}, out_stride = {s*d*e, d_hp*s*d*e, d*e}
+ *   replication (H_kv, s, d) -> (H_kv*rep, s, d): n = {H_kv, rep, s}, in_stride = {s*d*e, 0, d*e}
+ * Errors: LOONG_E_NULL, LOONG_E_SHAPE (negative sizes), LOONG_E_ALIGN.
+ */
+LOONG_API int loong_permute_rows(const int64_t n[3], const int64_t in_stride[3], const int64_t out_stride[3],
+                                 int64_t row_bytes, const void* in, void* out, void* stream);
+
+/*
+ * Gradient of the KV replication (paper: Sec. "KV Replication for GQA", backward pass): the fp32
+ * gradients of the `rep` copies of every head are added in copy order.
+ * in [heads*rep, rows_per_head*head_dim] fp32 contiguous -> out [heads, rows_per_head*head_dim].
+ * `elems_per_head` = rows_per_head*head_dim must be a multiple of 4; pointers 16-byte aligned;
+ * in and out must not overlap.  Errors: LOONG_E_NULL, LOONG_E_SHAPE, LOONG_E_ALIGN.
+ */
+LOONG_API int loong_reduce_replicas(int64_t heads, int32_t rep, int64_t elems_per_head, const float* in, float* out,
+                                    void* stream);
+
+/*
  * Performance model of 2D-Attention (paper: Sec. "Performance Analysis": "Computation
  * Analysis", "P2P Communication Analysis", "SeqAlltoAll Communication Analysis").  Host only.
  * Inputs: sequence length S and hidden size D (elements), H query heads, H_kv key/value

@@ -21,6 +21,7 @@ EXPORTS = (
     "loong_zigzag_mask", "loong_attn_step_fwd", "loong_lse_merge", "loong_attn_step_bwd",
     "loong_bwd_delta", "loong_init_running", "loong_finalize_out", "loong_validate_step",
     "loong_last_error", "loong_version", "loong_mfma_probe", "loong_cost_model", "loong_cost_search",
+    "loong_permute_rows", "loong_reduce_replicas",
 )
 
 
@@ -73,6 +74,8 @@ lib.loong_init_running.argtypes = [_i64, _i32, _vp, _vp, _vp]
 lib.loong_finalize_out.argtypes = [_i64, _i32, _vp, _vp, _i32, _vp]
 lib.loong_validate_step.argtypes = [C.POINTER(StepDesc)]
 lib.loong_mfma_probe.argtypes = [_i32, _i32, _vp, _vp]
+lib.loong_permute_rows.argtypes = [C.POINTER(_i64), C.POINTER(_i64), C.POINTER(_i64), _i64, _vp, _vp, _vp]
+lib.loong_reduce_replicas.argtypes = [_i64, _i32, _i64, _vp, _vp, _vp]
 lib.loong_cost_model.argtypes = [C.POINTER(CostIn), C.POINTER(CostOut)]
 lib.loong_cost_search.argtypes = [C.POINTER(CostIn), _i32, _i32, C.POINTER(CostIn), C.POINTER(CostOut)]
 lib.loong_last_error.restype = C.c_char_p
@@ -135,6 +138,16 @@ def cost_search(d_sp: int, max_w: int, **kw) -> dict:
     res = _as_dict(best_out)
     res.update(d_hp=best_in.d_hp, d_cp=best_in.d_cp, w=best_in.w)
     return res
+
+
+def permute_rows(n, in_stride, out_stride, row_bytes: int, src, dst, stream=None):
+    """loong_permute_rows: n, in_stride, out_stride are 3-sequences (strides in bytes)."""
+    a3 = _i64 * 3
+    _check(lib.loong_permute_rows(a3(*n), a3(*in_stride), a3(*out_stride), row_bytes, _ptr(src), _ptr(dst), _stream(stream)))
+
+
+def reduce_replicas(heads: int, rep: int, elems_per_head: int, src, dst, stream=None):
+    _check(lib.loong_reduce_replicas(heads, rep, elems_per_head, _ptr(src), _ptr(dst), _stream(stream)))
 
 
 def mfma_probe(workgroups: int, iters: int, sink, stream=None):

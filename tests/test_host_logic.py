@@ -125,3 +125,20 @@ def test_entry_points_fail_before_any_launch_on_bad_arguments():
 def test_error_text_is_per_call():
     assert P.validate_step(_good(head_dim=96)) != P.OK and "head_dim" in P.last_error()
     assert P.validate_step(_good()) == P.OK and P.last_error() == ""
+
+
+def test_layout_and_probe_entry_points_validate_before_touching_a_device():
+    import ctypes as C
+    lib = P.binding.lib
+    a3 = C.c_int64 * 3
+    ok = a3(16, 16, 16)
+    assert lib.loong_permute_rows(a3(1, 1, 1), ok, ok, 16, None, 0x1000, None) == P.E_NULL
+    assert lib.loong_permute_rows(a3(1, 1, 1), ok, a3(16, 16, 8), 16, 0x1000, 0x2000, None) == P.E_ALIGN
+    assert lib.loong_permute_rows(a3(1, 1, 1), ok, ok, 24, 0x1000, 0x2000, None) == P.E_ALIGN
+    assert lib.loong_permute_rows(a3(-1, 1, 1), ok, ok, 16, 0x1000, 0x2000, None) == P.E_SHAPE
+    assert lib.loong_permute_rows(a3(0, 1, 1), ok, ok, 16, 0x1000, 0x2000, None) == P.OK
+    assert lib.loong_reduce_replicas(2, 0, 4, 0x1000, 0x2000, None) == P.E_SHAPE
+    assert lib.loong_reduce_replicas(2, 2, 6, 0x1000, 0x2000, None) == P.E_ALIGN
+    assert lib.loong_reduce_replicas(0, 2, 4, 0x1000, 0x2000, None) == P.OK
+    assert lib.loong_mfma_probe(0, 1, 0x1000, None) == P.E_SHAPE
+    assert lib.loong_mfma_probe(1, 1, None, None) == P.E_NULL
