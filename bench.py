@@ -190,6 +190,41 @@ def main():
     merge_ms = timed(lambda: P.lse_merge(rows, cfg.d, run_out, run_lse, blk_out, blk_lse), 20)
     merge = {"rows": rows, "ms": round(merge_ms, 4), "bytes_per_row": 12 * cfg.d + 12,
              "GB_per_s": round(rows * (12 * cfg.d + 12) / (merge_ms * 1e-3) / 1e9, 1), "hbm_peak_GB_per_s": 8000}
+    # forward with the receive buffers of Alg. 2 (device-to-device copies on two side streams stand in
+    # for the inner- and outer-ring transfers) against the forward over resident chunks
+    fwd_resident_ms = timed(lambda: rep.forward(run.q, run.k_by_src, run.v_by_src), 5)
+    fwd_buffers_ms = timed(lambda: rep.forward_two_buffers(run.q, run.k_by_src, run.v_by_src), 5)
+    stage_k = torch.empty_like(run.k_by_src[0])
+    stage_v = torch.empty_like(run.v_by_src[0])
+    def copies():
+        for st in rep.plan:
+            stage_k.copy_(run.k_by_src[st["src_rank"]], non_blocking=True)
+            stage_v.copy_(run.v_by_src[st["src_rank"]], non_blocking=True)
+    copies_ms = timed(copies, 5)
+    two_buffers = {"fwd_ms_resident": round(fwd_resident_ms, 4), "fwd_ms_two_buffers": round(fwd_buffers_ms, 4),
+                   "copies_alone_ms": round(copies_ms, 4),
+                   "exposed_transfer_ms": round(max(0.0, fwd_buffers_ms - fwd_resident_ms), 4),
+                   "chunk_MiB": round(run.k_by_src[0].numel() * run.k_by_src.element_size() * 2 / 2**20, 1)}
+    # layout steps either side of the ring (HBM-bound, every byte read once and written once):
+    # 32 heads x 4096 tokens x 128 bf16 into 4 head-group messages and back into the ring layout,
+    # and the gradient reduction of 4-fold replicated KV heads
+    s_tok, Hh, dd, hp = 4096, 32, 128, 4
+    hl = Hh // hp
+    xin = torch.zeros(s_tok, Hh, dd, dtype=torch.bfloat16, device="cuda:0")
+    msg = torch.zeros(hp, hl, s_tok, dd, dtype=torch.bfloat16, device="cuda:0")
+    loc = torch.zeros(hl, hp * s_tok, dd, dtype=torch.bfloat16, device="cuda:0")
+    nbytes = xin.numel() * 2
+    pack_ms = timed(lambda: P.permute_rows((hp, hl, s_tok), (hl * dd * 2, dd * 2, Hh * dd * 2),
+                                           (hl * s_tok * dd * 2, s_tok * dd * 2, dd * 2), dd * 2, xin, msg), 20)
+    unpack_ms = timed(lambda: P.permute_rows((hp, hl, s_tok), (hl * s_tok * dd * 2, s_tok * dd * 2, dd * 2),
+                                             (s_tok * dd * 2, hp * s_tok * dd * 2, dd * 2), dd * 2, msg, loc), 20)
+    gin = torch.zeros(8 * 4, s_tok * dd, device="cuda:0")
+    gout = torch.zeros(8, s_tok * dd, device="cuda:0")
+    red_ms = timed(lambda: P.reduce_replicas(8, 4, s_tok * dd, gin, gout), 20)
+    layout = {"pack_heads_GB_per_s": round(2 * nbytes / (pack_ms * 1e-3) / 1e9, 1),
+              "unpack_tokens_GB_per_s": round(2 * nbytes / (unpack_ms * 1e-3) / 1e9, 1),
+              "reduce_replicas_GB_per_s": round((gin.numel() + gout.numel()) * 4 / (red_ms * 1e-3) / 1e9, 1),
+              "tensor_MiB": nbytes >> 20}
     # the matrix cores alone, at the clocks the chip really holds
     wgs, iters_probe = 256 * 8, 4000
     sink = torch.empty(wgs * 256, device="cuda:0")
@@ -215,6 +250,8 @@ def main():
         "kernels": per_kernel,
         "step_classes": step_classes,
         "merge_only": merge,
+        "layout_steps": layout,
+        "two_buffer_replay": two_buffers,
         "mfma_only_probe_tflops": round(mfma_sustained, 1),
         "pct_of_mfma_only_probe": round(100.0 * tflops / mfma_sustained, 2),
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),

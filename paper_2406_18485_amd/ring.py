@@ -96,3 +96,49 @@ class RingReplay:
             first = False
             B.attn_step_bwd(_desc(s, step, flags), q, k_by_src[src], v_by_src[src], self.o, d_o, self.lse,
                             self.delta, self.dq, self.dk[src], self.dv[src], stream)
+
+    # ---- forward with the receive buffers of Alg. 2: the chunk of the next micro-step arrives
+    # in an inner-ring buffer while the current one is used, and the first chunk of the next
+    # outer step arrives in the outer-ring buffer during the whole inner ring.  On one GPU the
+    # "transfers" are device-to-device copies from the resident chunks on two side streams
+    # (default priority), ordered against the step kernels with events exactly as the P2P
+    # receives would be.  Result: the same (out, lse, o) as forward().
+    def forward_two_buffers(self, q, k_by_src, v_by_src):
+        s = self.shape
+        main = torch.cuda.current_stream(self.dev)
+        if not hasattr(self, "_kv_bufs"):
+            shp = (s.batch, s.hkv, s.L, s.d)
+            self._kv_bufs = [(torch.empty(shp, dtype=self.store_dtype, device=self.dev),
+                              torch.empty(shp, dtype=self.store_dtype, device=self.dev)) for _ in range(3)]
+            self._comm = (torch.cuda.Stream(self.dev), torch.cuda.Stream(self.dev))   # inner ring, outer ring
+        bufs, (inner, outer) = self._kv_bufs, self._comm
+        filled = [torch.cuda.Event() for _ in range(3)]
+        released = [torch.cuda.Event() for _ in range(3)]
+
+        def receive(stream, b, src):
+            stream.wait_event(released[b])          # the buffer's last reader has finished
+            with torch.cuda.stream(stream):
+                bufs[b][0].copy_(k_by_src[src], non_blocking=True)
+                bufs[b][1].copy_(v_by_src[src], non_blocking=True)
+                filled[b].record(stream)
+
+        B.init_running(self.rows, s.d, self.out, self.lse)
+        for ev in released:
+            ev.record(main)
+        cur, nxt, out = 0, 1, 2
+        receive(inner, cur, self.plan[0]["src_rank"])   # the own chunk
+        n_outer = s.cp // s.w
+        for t, step in enumerate(self.plan):
+            a, b = divmod(t, s.w)
+            if b == 0 and a + 1 < n_outer:
+                receive(outer, out, self.plan[(a + 1) * s.w]["src_rank"])
+            if b + 1 < s.w:
+                receive(inner, nxt, self.plan[t + 1]["src_rank"])
+            main.wait_event(filled[cur])
+            B.attn_step_fwd(_desc(s, step, B.FUSE_MERGE), q, bufs[cur][0], bufs[cur][1], self.out, self.lse)
+            released[cur].record(main)
+            if b + 1 < s.w:
+                cur, nxt = nxt, cur
+            else:
+                cur, out = out, cur
+        B.finalize_out(self.rows, s.d, self.out, self.o, s.dtype)

@@ -150,6 +150,22 @@ def test_forward_is_bit_reproducible_and_order_of_visits_does_not_matter():
     assert max_abs(dk_a, dk_l) < 2e-3 and max_abs(dv_a, dv_l) < 2e-3 and max_abs(a.dq(), lin.dq()) < 2e-3
 
 
+@pytest.mark.parametrize("idx,c", [(3, 192), (1, 128), (2, 160)])
+def test_two_buffer_forward_equals_the_resident_replay(idx, c):
+    """The receive-buffer schedule of Alg. 2 (inner and outer ring buffers, copies on side streams) must give
+    bit-identical results to the replay over resident chunks: same kernels, same data, only the event ordering differs."""
+    cfg = CONFIGS[idx].shrunk(c)
+    run = Replayed(cfg, make_inputs(cfg))
+    run.rep.forward(run.q, run.k_by_src, run.v_by_src)
+    torch.cuda.synchronize()
+    ref = (run.rep.out.clone(), run.rep.lse.clone(), run.rep.o.clone())
+    for _ in range(2):   # twice: the buffers and streams are reused
+        run.rep.out.fill_(7.0)
+        run.rep.forward_two_buffers(run.q, run.k_by_src, run.v_by_src)
+        torch.cuda.synchronize()
+        assert torch.equal(run.rep.out, ref[0]) and torch.equal(run.rep.lse, ref[1]) and torch.equal(run.rep.o, ref[2])
+
+
 # ------------------------------------------------------------------------------ direct calls, edge cases
 def _direct(dtype, b, hq, hkv, d, nq, nk, seed, strided=False, accum=False):
     rng = np.random.default_rng(seed)
