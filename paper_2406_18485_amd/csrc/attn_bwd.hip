@@ -3,26 +3,31 @@
 // Sec. "Selective Checkpoint++").  This step's share of dQ comes from the row-owning pass
 // in attn_bwd_dq.hip, launched right after this kernel.
 //
-// Work split.  A workgroup of 4 waves (one per SIMD, up to 512 registers each) owns 128 keys
-// of one kv head, 32 per wave, and walks over the 64-row query tiles of every q head of
-// the group that can see them.  Loop-invariant in registers: the wave's K and V rows as B
-// operands of S = Q K^T and dP = dO V^T (V negated, see below) and the fp32 dK / dV
-// accumulators.
+// Work split.  A workgroup owns 128 keys of one kv head and walks over the 64-row query
+// tiles of every q head of the group that can see them.  It has eight waves, two per SIMD:
+// for each group of 32 keys a "P wave" and an "E wave" that sit on the same SIMD.
+//   P wave   keeps the K rows (B operand) and the fp32 dV accumulator of its 32 keys:
+//            S = Q K^T, P = exp2(S * scale * log2 e - LSE * log2 e), packed to bf16, handed
+//            to its partner through LDS, then dV += P^T dO;
+//   E wave   keeps the -V rows and the fp32 dK accumulator: T = delta - dO V^T straight out
+//            of the matrix cores (the chain starts from C = delta), then E = P o T
+//            (= -dS / scale), dK += E^T Q; dK is multiplied by -scale once, at the end.
+// The E waves run one tile behind the P waves (P of tile t is consumed in the next iteration,
+// from a double-buffered hand-over area; the query tiles stay in LDS for three iterations), so
+// one workgroup barrier per tile suffices and neither role ever waits for the other.  The E
+// waves, which have less element-wise work, also issue the staging loads.
+// Splitting the roles halves the registers a wave must hold (so two waves fit a SIMD), and
+// the two waves of a SIMD are in different kinds of work at any time: the vector issue port,
+// which the matrix instructions share with the element-wise ones, is the unit that bounds
+// this kernel, and every other instruction of one wave (LDS reads, waits, staging, scalar
+// work) now hides behind the partner.
 //
 // Per query tile: Q, dO (row-major) and the rows' LSE and delta go from global memory
 // straight into LDS, one tile ahead, with the 16-byte pieces of every row XOR-permuted so
-// that both kinds of LDS read below are free of bank conflicts.
-//   S, T      A operand = 16-byte reads of Q / dO rows; accumulators put one key per lane
-//             and 16 query rows per 32x32 block in registers.  T = delta - dP comes out of
-//             the matrix cores directly: the chain starts from C = delta and multiplies
-//             by -V;
-//   P         exp2(S * scale * log2 e - LSE * log2 e);  E = P o T = -dS / scale;
-//   dV, dK    contraction over rows: A operand = P^T / E^T straight from those
-//             accumulators (packed to bf16), B operand = transposing LDS reads of the same
-//             dO / Q tiles; dK is multiplied by -scale once, at the end.
-// The tile's two 32-row blocks are software-pipelined: the element-wise work on one block is
-// written between the matrix instructions of the other, so both units stay busy although a
-// SIMD holds a single wave.
+// that both kinds of LDS read are free of bank conflicts: A operands of S / T are 16-byte
+// reads of Q / dO rows (one key per lane, 16 query rows per 32x32 block in registers);
+// the contractions over rows take P^T / E^T straight from registers as the A operand and
+// transposing LDS reads of the same dO / Q tiles as the B operand.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -49,8 +54,8 @@ struct BwdParams {
   WorkMap map;     // units = batch x kv heads, items = key tiles x splits
 };
 
-constexpr int kBwdWaves = 4;
-constexpr int kBwdBN = 32 * kBwdWaves;  // keys per workgroup
+constexpr int kBwdWaves = 8;            // 4 key groups x {P wave, E wave}
+constexpr int kBwdBN = 128;             // keys per workgroup
 constexpr int kBwdBM = 64;              // query rows per iteration
 
 template <int D>
@@ -60,9 +65,12 @@ struct BwdCfg {
   static constexpr int CH = D / 8;                 // 16-byte pieces per row
   static constexpr int RPI = 1024 / ROWB;          // rows filled by one wave-level load
   static constexpr int QT_B = BM * ROWB;           // bytes of a Q (or dO) tile
-  static constexpr int LI = QT_B / 1024 / kBwdWaves;  // loads per wave per Q (or dO) tile
+  static constexpr int LI = QT_B / 1024 / 4;       // loads per staging wave (the four E waves) per Q (or dO) tile
   static constexpr int STAGE_B = 2 * QT_B + 2 * BM * 4;  // Q, dO, lse, delta
-  static constexpr int SMEM_BYTES = 2 * STAGE_B;
+  static constexpr int NSTAGE = 3;                 // tile being staged, tile of the P waves, tile of the E waves
+  static constexpr int XCH_B = 4 * 2 * 2 * 1024;   // P hand-over: 4 key groups x 2 blocks x 2 halves x 64 lanes x 16 B
+  static constexpr int SMEM_BYTES = NSTAGE * STAGE_B + 2 * XCH_B;
+  static_assert(LI >= 1 && LI * 1024 * 4 == QT_B, "tile must split evenly over the staging waves");
 };
 
 template <int D>
@@ -83,7 +91,9 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
   const Segment kseg = kb ? p.g.k[1] : p.g.k[0];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hh = lane >> 5;
-  const int my_koff = koff0 + 32 * wave + l32;
+  const int kg = wave & 3;           // key group: keys koff0 + 32 kg ..
+  const bool p_wave = wave < 4;      // waves kg and kg + 4 share a SIMD
+  const int my_koff = koff0 + 32 * kg + l32;
   const bool key_ok = my_koff < kseg.len;
   const int64_t my_krow = kseg.start + min(my_koff, kseg.len - 1);
 
@@ -113,25 +123,24 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
     h = hk * p.G + cu.gq;
   };
 
-  // ---- K and V rows of this wave as B operands (row my_krow, columns 16 ks + 8 hh .. +7);
-  // V with the sign bits flipped
-  bf16x8_t kf[NKS], vfn[NKS];
+  // ---- the wave's B operand: its K rows (P wave) or its V rows with the sign bits flipped
+  // (E wave); row my_krow, columns 16 ks + 8 hh .. +7
+  bf16x8_t bfrag[NKS];
   {
-    const uint16_t* krow = p.k + b * p.ks[0] + hk * p.ks[1] + my_krow * p.ks[2];
-    const uint16_t* vrow = p.v + b * p.ks[0] + hk * p.ks[1] + my_krow * p.ks[2];
+    const uint16_t* row = (p_wave ? p.k : p.v) + b * p.ks[0] + hk * p.ks[1] + my_krow * p.ks[2];
+    const uint32_t flip = p_wave ? 0u : 0x80008000u;
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
-      kf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(krow + ks * 16 + hh * 8));
-      uint4 x = *reinterpret_cast<const uint4*>(vrow + ks * 16 + hh * 8);
-      x.x ^= 0x80008000u; x.y ^= 0x80008000u; x.z ^= 0x80008000u; x.w ^= 0x80008000u;
-      vfn[ks] = as_bf16x8(x);
+      uint4 x = *reinterpret_cast<const uint4*>(row + ks * 16 + hh * 8);
+      x.x ^= flip; x.y ^= flip; x.z ^= flip; x.w ^= flip;
+      bfrag[ks] = as_bf16x8(x);
     }
   }
 
   // ---- per-lane pieces of the staging and of the LDS reads
   const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
-  // direct loads: load i of this wave fills LDS bytes [(wave + 4 i) * 1024, +1024) of a tile
-  const int ld_row = wave * C::RPI + lane / CH;  // row inside the tile for i = 0; later loads add 4 * RPI rows
+  // direct loads (E waves): load i of staging wave kg fills LDS bytes [(kg + 4 i) * 1024, +1024) of a tile
+  const int ld_row = kg * C::RPI + lane / CH;  // row inside the tile for i = 0; later loads add 4 * RPI rows
   const uint32_t ld_piece = (uint32_t)((lane % CH) ^ tile_swizzle<D>(ld_row)) * 16;
   const uint32_t q_rowbytes = (uint32_t)p.qs[2] * 2;  // validated: token stride < 2^24 elements
   uint32_t ld_off[LI];  // byte offset of this lane's piece from the tile's first row
@@ -151,15 +160,18 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
     tr_lo[db] = (4 * hh + tr_r) * ROWB + (piece ^ tile_swizzle<D>(4 * hh + tr_r)) * 16 + (tr_q & 1) * 8;
     tr_hi[db] = (4 * hh + tr_r + 8) * ROWB + (piece ^ tile_swizzle<D>(4 * hh + tr_r + 8)) * 16 + (tr_q & 1) * 8;
   }
+  // P hand-over slot of this key group: [block][half of the block's 16 elements][lane] x 16 bytes
+  unsigned char* const xch = smem + C::NSTAGE * C::STAGE_B + kg * 4096 + lane * 16;
 
-  floatx16_t dk[NDB], dv[NDB];
+  floatx16_t acc[NDB];  // dV (P wave) or dK / -scale (E wave) of the wave's 32 keys
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { dk[db][v] = 0.f; dv[db][v] = 0.f; }
+    for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
 
-  // ---- staging of one query tile: Q, dO rows and their LSE / delta, global -> LDS
+  // ---- staging of one query tile by the E waves: Q, dO rows and their LSE / delta, global -> LDS
   auto issue_tile = [&](const Cursor& cu, int stage) {
+    if (p_wave) return;
     int h, qa, i0;
     decode(cu, h, qa, i0);
     const int qlen = qa ? qlen1 : qlen0, qstart = qa ? qstart1 : qstart0;
@@ -171,20 +183,20 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
     if (last >= BM - 1) {
 #pragma unroll
       for (int i = 0; i < LI; ++i) {
-        load_to_lds_16(qb, ld_off[i], st + (wave + 4 * i) * 1024);
-        load_to_lds_16(ob, ld_off[i], st + C::QT_B + (wave + 4 * i) * 1024);
+        load_to_lds_16(qb, ld_off[i], st + (kg + 4 * i) * 1024);
+        load_to_lds_16(ob, ld_off[i], st + C::QT_B + (kg + 4 * i) * 1024);
       }
     } else {  // ragged end of a segment: rows past the last one repeat it
 #pragma unroll
       for (int i = 0; i < LI; ++i) {
         const uint32_t off = (uint32_t)min(ld_row + i * 4 * C::RPI, last) * q_rowbytes + ld_piece;
-        load_to_lds_16(qb, off, st + (wave + 4 * i) * 1024);
-        load_to_lds_16(ob, off, st + C::QT_B + (wave + 4 * i) * 1024);
+        load_to_lds_16(qb, off, st + (kg + 4 * i) * 1024);
+        load_to_lds_16(ob, off, st + C::QT_B + (kg + 4 * i) * 1024);
       }
     }
-    if (wave < 2) {  // wave 0: the 64 rows' LSE, wave 1: their delta
+    if (kg < 2) {  // E wave 0: the 64 rows' LSE, E wave 1: their delta
       const int64_t row = ((int64_t)b * p.Hq + h) * p.q_len + qstart + i0 + min(lane, last);
-      load_to_lds_4((wave ? p.delta : p.lse) + row, st + 2 * C::QT_B + wave * BM * 4);
+      load_to_lds_4((kg ? p.delta : p.lse) + row, st + 2 * C::QT_B + kg * BM * 4);
     }
   };
 
@@ -193,143 +205,174 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
   cur.r = it_begin - cur.gq * per_g;
   nxt = cur;
 
-  wait_vmcnt<0>();  // K / V fragments are in: no counter wait of the compiler's lands in the loop
+  wait_vmcnt<0>();  // the K / V fragments are in: no counter wait of the compiler's lands in the loop
   if (it_begin < it_end) issue_tile(cur, 0);
   wait_vmcnt<0>();
 
-  int stage = 0;
-  for (int it = it_begin; it < it_end; ++it, stage ^= 1, advance(cur)) {
-    // the accumulators live in the accumulation registers for the whole loop (a hint: nothing
-    // is emitted here, but the register allocator may not park them among the vector registers)
-#pragma unroll
-    for (int db = 0; db < NDB; ++db) asm volatile("" : "+a"(dk[db]), "+a"(dv[db]));
-    __syncthreads();  // tile `it` is in LDS (each wave waited for its part); iteration it - 1 is finished
+  constexpr int PF = 2;  // LDS operands are requested PF matrix steps ahead
+  // Iteration j: the P waves work on tile j, the E waves on tile j - 1, tile j + 1 is staged.
+  int st_p = 0, st_e = 2, st_n = 1;  // LDS stages of those three tiles
+  for (int it = it_begin; it <= it_end && it_begin < it_end; ++it) {
+    __syncthreads();  // tile `it` is in LDS, P of tile it - 1 is handed over, tile it - 2 is finished with
     if (it + 1 < it_end) {
       advance(nxt);
-      issue_tile(nxt, stage ^ 1);
+      issue_tile(nxt, st_n);
     }
+    const bool p_active = p_wave && it < it_end, e_active = !p_wave && it > it_begin;
     int h, qa, i0;
     decode(cur, h, qa, i0);
     const int qlen = qa ? qlen1 : qlen0;
     const bool isdiag = (qa ? clsq1 : clsq0) == LOONG_DIAG;
     const bool need_mask = i0 + BM > qlen || koff0 + BN > kseg.len || (isdiag && i0 < koff0 + BN - 1);
-    const unsigned char* Qt = smem + stage * C::STAGE_B;
+    const unsigned char* Qt = smem + (p_wave ? st_p : st_e) * C::STAGE_B;
     const unsigned char* Ot = Qt + C::QT_B;
     const float* lse_s = reinterpret_cast<const float*>(Qt + 2 * C::QT_B);
     const float* dl_s = lse_s + BM;
+    unsigned char* const xch_w = xch + ((it - it_begin) & 1) * C::XCH_B;        // P of tile `it`
+    const unsigned char* const xch_r = xch + ((it - it_begin + 1) & 1) * C::XCH_B;  // P of tile it - 1
 
-    // One tile.  Block ib = rows 32 ib .. 32 ib + 31; register v of an accumulator is row
-    // acc_row(v, hh) of the block.  The tile is a sequence of 4 NS matrix steps: S and T of
-    // block 0 (alternating), of block 1, then dV and dK with block 0, with block 1; the
-    // LDS operands are requested a batch of PF steps ahead (one counter wait per batch), and
-    // the element-wise work on block 0 (1) is spread over the steps of the second (third)
-    // quarter.
-    constexpr int NS = 2 * NKS;    // matrix steps per quarter (== 4 * NDB)
-    constexpr int EPS = 16 / NS;   // elements per matrix step
-    constexpr int PF = 4;          // operands are read in batches of PF, one batch ahead of their use
-    static_assert(NS == 4 * NDB && EPS * NS == 16, "quarters of equal length");
-    floatx16_t s[2], t[2];
-    float nl[2][16];
-    uint32_t pw[2][8], ew[2][8];  // P and E = P o T, two bf16 per word: elements 2 w, 2 w + 1
-    // C operand of the T chains (the rows' delta) and exponent offsets -LSE log2 e
+    // Block ib = rows 32 ib .. 32 ib + 31 of the tile; register v of an accumulator is row
+    // acc_row(v, hh) of the block.  pw / ew: P and E = P o T packed, two bf16 per word
+    // (elements 2 w, 2 w + 1).
+    floatx16_t st2[2];
+    uint32_t w2[2][8];
+    // 2 NKS matrix steps of S (P wave: Q rows, K fragments) or T (E wave: dO rows, -V fragments)
+    // of both blocks, block 1 after block 0; `between(k)` is called after step k.
+    auto rows_product = [&](const unsigned char* tile, auto&& between) {
+      auto operand = [&](int k) {
+        return as_bf16x8(*reinterpret_cast<const uint4*>(tile + (k / NKS) * 32 * ROWB + row_rd[k % NKS]));
+      };
+      bf16x8_t ring[PF + 1];
+      static_for<0, PF>([&](auto kc) { ring[kc.value] = operand(kc.value); });
+      static_for<0, 2 * NKS>([&](auto kc) {
+        constexpr int k = decltype(kc)::value, ib = k / NKS, ks = k % NKS;
+        if constexpr (k + PF < 2 * NKS) ring[(k + PF) % (PF + 1)] = operand(k + PF);
+        if constexpr (ks == 0 && true) {
+          if (p_wave) {
+            floatx16_t zero;
 #pragma unroll
-    for (int ib = 0; ib < 2; ++ib)
-#pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        const float4 L = *reinterpret_cast<const float4*>(&lse_s[ib * 32 + 8 * vq + 4 * hh]);
-        const float4 Dl = *reinterpret_cast<const float4*>(&dl_s[ib * 32 + 8 * vq + 4 * hh]);
-        nl[ib][4 * vq + 0] = L.x * -kLog2e; nl[ib][4 * vq + 1] = L.y * -kLog2e;
-        nl[ib][4 * vq + 2] = L.z * -kLog2e; nl[ib][4 * vq + 3] = L.w * -kLog2e;
-        t[ib][4 * vq + 0] = Dl.x; t[ib][4 * vq + 1] = Dl.y; t[ib][4 * vq + 2] = Dl.z; t[ib][4 * vq + 3] = Dl.w;
-      }
-    if (need_mask) {  // masked pairs get the exponent offset -inf: P = 0 whatever the score
+            for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+            st2[ib] = mfma32(ring[k % (PF + 1)], bfrag[0], zero);
+          } else {
+            st2[ib] = mfma32(ring[k % (PF + 1)], bfrag[0], st2[ib]);  // C = delta
+          }
+        } else {
+          st2[ib] = mfma32(ring[k % (PF + 1)], bfrag[ks], st2[ib]);
+        }
+        between(kc);
+        __builtin_amdgcn_sched_barrier(0);  // keep the operand reads ahead of their use
+      });
+    };
+    // 4 NDB matrix steps of acc += W^T X over the tile's 64 rows (W = pw or ew, X = dO or Q tile).
+    // Element e of the A operand is row 16 sl + 8 (e / 4) + 4 hh + e % 4 of its block, so the
+    // B operand is the run of four rows starting at 16 sl + 4 hh and the run 8 rows on.
+    auto cols_product = [&](const unsigned char* tile, auto&& before) {
+      auto operand = [&](int k) {
+        const int ib = k / (2 * NDB), sl = (k / NDB) % 2, db = k % NDB;
+        const unsigned char* base = tile + (ib * 32 + sl * 16) * ROWB;
+        return read_tr_pair(base + tr_lo[db], base + tr_hi[db]);
+      };
+      bf16x8_t ring[PF + 1];
+      static_for<0, PF>([&](auto kc) { ring[kc.value] = operand(kc.value); });
+      static_for<0, 4 * NDB>([&](auto kc) {
+        constexpr int k = decltype(kc)::value, ib = k / (2 * NDB), sl = (k / NDB) % 2, db = k % NDB;
+        if constexpr (k + PF < 4 * NDB) ring[(k + PF) % (PF + 1)] = operand(k + PF);
+        before(kc);
+        const bf16x8_t a = as_bf16x8(make_uint4(w2[ib][4 * sl], w2[ib][4 * sl + 1], w2[ib][4 * sl + 2], w2[ib][4 * sl + 3]));
+        acc[db] = mfma32(a, ring[k % (PF + 1)], acc[db]);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    };
+
+    if (p_active) {
+      // exponent offsets -LSE log2 e; masked pairs get -inf: P = 0 whatever the score
+      float nl[2][16];
 #pragma unroll
       for (int ib = 0; ib < 2; ++ib)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int i_off = i0 + ib * 32 + acc_row(v, hh);
-          const bool ok = key_ok && i_off < qlen && (!isdiag || my_koff <= i_off);
-          nl[ib][v] = ok ? nl[ib][v] : -INFINITY;
+        for (int vq = 0; vq < 4; ++vq) {
+          const float4 L = *reinterpret_cast<const float4*>(&lse_s[ib * 32 + 8 * vq + 4 * hh]);
+          nl[ib][4 * vq + 0] = L.x * -kLog2e; nl[ib][4 * vq + 1] = L.y * -kLog2e;
+          nl[ib][4 * vq + 2] = L.z * -kLog2e; nl[ib][4 * vq + 3] = L.w * -kLog2e;
         }
-    }
-    // LDS operand of matrix step k: a 16-byte piece of a Q / dO row, or two transposing reads
-    // (element e of the A operand of dV / dK is row 16 sl + 8 (e / 4) + 4 hh + e % 4 of its
-    // block, so the B operand is the run of four rows starting at 16 sl + 4 hh and the run
-    // 8 rows on)
-    auto operand = [&](int k) -> bf16x8_t {
-      const int quarter = k / NS, j = k % NS, second = j & 1;
-      if (quarter < 2)
-        return as_bf16x8(*reinterpret_cast<const uint4*>((second ? Ot : Qt) + quarter * 32 * ROWB + row_rd[j / 2]));
-      const int sl = j / (2 * NDB), db = (j / 2) % NDB;
-      const unsigned char* base = (second ? Qt : Ot) + ((quarter - 2) * 32 + sl * 16) * ROWB;
-      return read_tr_pair(base + tr_lo[db], base + tr_hi[db]);
-    };
-    auto matrix_step = [&](int k, bf16x8_t op) {
-      const int quarter = k / NS, j = k % NS, second = j & 1;
-      if (quarter < 2) {
-        const int ib = quarter, ks = j / 2;
-        floatx16_t zero;
+      if (need_mask) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) zero[v] = 0.f;
-        if (second) t[ib] = mfma32(op, vfn[ks], t[ib]);
-        else s[ib] = mfma32(op, kf[ks], ks ? s[ib] : zero);
-      } else {
-        const int ib = quarter - 2, sl = j / (2 * NDB), db = (j / 2) % NDB;
-        const uint32_t* w = second ? ew[ib] : pw[ib];
-        const bf16x8_t a = as_bf16x8(make_uint4(w[4 * sl], w[4 * sl + 1], w[4 * sl + 2], w[4 * sl + 3]));
-        if (second) dk[db] = mfma32(a, op, dk[db]);
-        else dv[db] = mfma32(a, op, dv[db]);
+        for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int i_off = i0 + ib * 32 + acc_row(v, hh);
+            const bool ok = key_ok && i_off < qlen && (!isdiag || my_koff <= i_off);
+            nl[ib][v] = ok ? nl[ib][v] : -INFINITY;
+          }
       }
-    };
-    float p_even = 0.f, e_even = 0.f;
-    auto element = [&](int ib, int v) {
-      const float pv = fast_exp2(fmaf(s[ib][v], p.c, nl[ib][v]));
-      const float ev = pv * t[ib][v];
-      if (v & 1) {
-        pw[ib][v / 2] = pack_bf16x2(p_even, pv);
-        ew[ib][v / 2] = pack_bf16x2(e_even, ev);
-      } else {
-        p_even = pv;
-        e_even = ev;
-      }
-    };
-    bf16x8_t ring[2 * PF];
-    static_for<0, PF>([&](auto kc) { ring[kc.value] = operand(kc.value); });
-    static_for<0, 4 * NS>([&](auto kc) {
-      constexpr int k = decltype(kc)::value;
-      if constexpr (k % PF == 0) {
-        static_for<k + PF, (k + 2 * PF < 4 * NS ? k + 2 * PF : 4 * NS)>(
-            [&](auto nc) { ring[nc.value % (2 * PF)] = operand(nc.value); });
-      }
-      matrix_step(k, ring[k % (2 * PF)]);
-      constexpr int quarter = k / NS, j = k % NS;
-      if constexpr (quarter == 1 || quarter == 2) {
-        static_for<0, EPS>([&](auto uc) { element(quarter - 1, j * EPS + uc.value); });
-      }
-      __builtin_amdgcn_sched_barrier(0);  // keep the operand reads ahead of their use
-    });
+      auto exps = [&](int ib, int w) {  // elements 2 w, 2 w + 1 of block ib
+        const float p0 = fast_exp2(fmaf(st2[ib][2 * w], p.c, nl[ib][2 * w]));
+        const float p1 = fast_exp2(fmaf(st2[ib][2 * w + 1], p.c, nl[ib][2 * w + 1]));
+        w2[ib][w] = pack_bf16x2(p0, p1);
+      };
+      // S of both blocks; the exponentials of block 0 between the matrix steps of block 1
+      rows_product(Qt, [&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        if constexpr (k >= NKS) static_for<0, 8 / NKS>([&](auto uc) { exps(0, (k - NKS) * (8 / NKS) + uc.value); });
+      });
+#pragma unroll
+      for (int w = 0; w < 8; ++w) exps(1, w);
+      // hand P to the partner wave
+#pragma unroll
+      for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+          *reinterpret_cast<uint4*>(xch_w + (ib * 2 + hf) * 1024) =
+              make_uint4(w2[ib][4 * hf], w2[ib][4 * hf + 1], w2[ib][4 * hf + 2], w2[ib][4 * hf + 3]);
+      cols_product(Ot, [](auto) {});  // dV += P^T dO
+    } else if (e_active) {
+      // T = delta - dO V^T: the chains start from the rows' delta
+#pragma unroll
+      for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          const float4 Dl = *reinterpret_cast<const float4*>(&dl_s[ib * 32 + 8 * vq + 4 * hh]);
+          st2[ib][4 * vq + 0] = Dl.x; st2[ib][4 * vq + 1] = Dl.y; st2[ib][4 * vq + 2] = Dl.z; st2[ib][4 * vq + 3] = Dl.w;
+        }
+      rows_product(Ot, [](auto) {});
+      uint32_t pw[2][8];
+#pragma unroll
+      for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          const uint4 x = *reinterpret_cast<const uint4*>(xch_r + (ib * 2 + hf) * 1024);
+          pw[ib][4 * hf] = x.x; pw[ib][4 * hf + 1] = x.y; pw[ib][4 * hf + 2] = x.z; pw[ib][4 * hf + 3] = x.w;
+        }
+      auto etimes = [&](int ib, int w) {  // E = P o T for elements 2 w, 2 w + 1 of block ib
+        w2[ib][w] = pack_bf16x2(bf16_lo(pw[ib][w]) * st2[ib][2 * w], bf16_hi(pw[ib][w]) * st2[ib][2 * w + 1]);
+      };
+#pragma unroll
+      for (int w = 0; w < 8; ++w) etimes(0, w);
+      // dK += E^T Q; the products of block 1 between the matrix steps of block 0
+      cols_product(Qt, [&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        if constexpr (k < 2 * NDB) static_for<0, 8 / (2 * NDB)>([&](auto uc) { etimes(1, k * (8 / (2 * NDB)) + uc.value); });
+      });
+    }
     wait_vmcnt<0>();  // this wave's part of the next tile, issued a whole iteration ago
+    if (it < it_end) advance(cur);
+    const int freed = st_e;
+    st_e = st_p; st_p = st_n; st_n = freed;
   }
 
-  // ---- dV and dK = -scale * (accumulated E^T Q) of this wave's 32 keys: a lane owns one
-  // column per block and 16 key rows
-  float* dk_base = p.dk + (((int64_t)b * p.Hkv + hk) * p.kv_len + kseg.start) * D + l32;
-  float* dv_base = p.dv + (((int64_t)b * p.Hkv + hk) * p.kv_len + kseg.start) * D + l32;
-  const float ns = -p.scale;
+  // ---- dV (P waves) and dK = -scale * (accumulated E^T Q) (E waves) of the wave's 32 keys:
+  // a lane owns one column per block and 16 key rows
+  float* base = (p_wave ? p.dv : p.dk) + (((int64_t)b * p.Hkv + hk) * p.kv_len + kseg.start) * D + l32;
+  const float f = p_wave ? 1.f : -p.scale;
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int koff = koff0 + 32 * wave + acc_row(v, hh);
+      const int koff = koff0 + 32 * kg + acc_row(v, hh);
       if (koff < kseg.len) {
         const int64_t o = (int64_t)koff * D + db * 32;
-        if (p.add_dkv) {
-          unsafeAtomicAdd(dk_base + o, dk[db][v] * ns);
-          unsafeAtomicAdd(dv_base + o, dv[db][v]);
-        } else {
-          dk_base[o] = dk[db][v] * ns;
-          dv_base[o] = dv[db][v];
-        }
+        if (p.add_dkv) unsafeAtomicAdd(base + o, acc[db][v] * f);
+        else base[o] = acc[db][v] * f;
       }
     }
 }
