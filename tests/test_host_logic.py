@@ -142,3 +142,27 @@ def test_layout_and_probe_entry_points_validate_before_touching_a_device():
     assert lib.loong_reduce_replicas(0, 2, 4, 0x1000, 0x2000, None) == P.OK
     assert lib.loong_mfma_probe(0, 1, 0x1000, None) == P.E_SHAPE
     assert lib.loong_mfma_probe(1, 1, None, None) == P.E_NULL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
+
+
+def test_package_fails_loudly_without_the_library(tmp_path):
+    """A copy of the package without libloong.so: the build module imports, anything else raises ImportError."""
+    import shutil
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = tmp_path / "paper_2406_18485_amd"
+    shutil.copytree(os.path.join(root, "paper_2406_18485_amd"), pkg,
+                    ignore=shutil.ignore_patterns("*.so", "_build", "__pycache__"))
+    code = ("import paper_2406_18485_amd as P\n"
+            "import paper_2406_18485_amd.build\n"
+            "try:\n    P.version()\n    print('NO ERROR')\nexcept ImportError as e:\n    print('ImportError', 'no fallback' in str(e))\n")
+    r = subprocess.run([sys.executable, "-c", code], cwd=tmp_path, capture_output=True, text=True, timeout=120)
+    assert r.stdout.strip() == "ImportError True", r.stdout + r.stderr
