@@ -121,6 +121,30 @@ def test_bf16_small_shapes_full_parity(hq, hkv, d, c, cp, w, rank):
     check_full(run.run(fuse_merge=False), ref)
 
 
+def _drawn_shapes(n, seed):
+    """Seeded draw of ring shapes: group sizes 1..8, both head dims, chunk lengths around the
+    32-, 64- and 128-token tile edges, every ring factorisation of cp, any rank."""
+    rng = np.random.default_rng(seed)
+    edges = [31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 255, 256, 300]
+    out = []
+    for _ in range(n):
+        hkv = int(rng.integers(1, 3))
+        group = int(rng.choice([1, 2, 3, 4, 8]))
+        cp = int(rng.choice([2, 3, 4, 6]))
+        w = int(rng.choice([x for x in range(1, cp + 1) if cp % x == 0]))
+        out.append((hkv * group, hkv, int(rng.choice([64, 128])), int(rng.choice(edges)), cp, w,
+                    int(rng.integers(0, cp))))
+    return out
+
+
+@pytest.mark.parametrize("hq,hkv,d,c,cp,w,rank", _drawn_shapes(14, seed=20240626))
+def test_bf16_drawn_shapes_full_parity(hq, hkv, d, c, cp, w, rank):
+    cfg = RingConfig(f"drawn_h{hq}_{hkv}_d{d}_c{c}_cp{cp}w{w}_r{rank}", cp=cp, w=w, rank=rank, hq=hq, hkv=hkv,
+                     d=d, c=c, dtype="bf16", sigma=0.8, seed=5 * c + rank)
+    inp = make_inputs(cfg)
+    check_full(Replayed(cfg, inp).run(), oracle_full(cfg, inp))
+
+
 @pytest.mark.parametrize("idx", [1, 2, 3, 4])
 @pytest.mark.parametrize("which_rank", ["first", "middle"])
 def test_shrunken_benchmark_configs_full_parity(idx, which_rank):
