@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=-1,
                     help="rows of the oracle sample (0: skip the CPU baseline; -1: sized for about 15 s of host work)")
     ap.add_argument("--unfused", action="store_true", help="run Attention and Update as separate kernels")
+    ap.add_argument("--dtype", choices=["bf16", "fp16"], default=None,
+                    help="storage type of q, k, v, o, d_o (default: the workload's, bf16); fp16 runs the same kernels "
+                         "with the fp16 matrix instruction (same 2.5 PFLOP/s peak)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="launch only device-to-device copies of 256 MiB (reference for the HBM byte counters) and exit")
     args = ap.parse_args()
@@ -86,6 +89,9 @@ def main():
     from workloads import CONFIGS, make_inputs
 
     cfg = CONFIGS[args.config]
+    if args.dtype and cfg.dtype != "fp32":
+        import dataclasses
+        cfg = dataclasses.replace(cfg, dtype=args.dtype)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.copy_calibration:
         # one elementwise copy kernel reads 256 MiB and writes 256 MiB per launch
@@ -235,7 +241,7 @@ def main():
         "metric": "fwd+bwd ring-step attention TFLOP/s on 1 GPU; % of bf16 MFMA peak",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "dtype": {"bf16": "bf16", "fp16": "f16", "fp32": "f32"}[cfg.dtype], "data": "synthetic",
         "config": {"workload": cfg.name, "cp": cfg.cp, "inner_ring": cfg.w, "rank": cfg.rank, "q_heads": cfg.hq,
                    "kv_heads": cfg.hkv, "head_dim": cfg.d, "local_tokens": cfg.L, "total_seq": cfg.S,
                    "ring_steps": cfg.cp, "update": "fused" if fuse else "separate kernel",

@@ -49,6 +49,8 @@ extern "C" {
 /* storage type of q, k, v, o, d_o */
 #define LOONG_BF16 0              /* bf16 MFMA kernels, head_dim 64 or 128 */
 #define LOONG_FP32 1              /* plain fp32 kernels (small cases), head_dim <= 128, multiple of 4 */
+#define LOONG_FP16 2              /* the MFMA kernels on IEEE half storage (the 16-bit type Sec. "Performance
+                                     Analysis" sizes the tensors in), head_dim 64 or 128 */
 
 /* class of a (q half, k half) block of one micro-step */
 #define LOONG_SKIP 0              /* key chunk lies after the query chunk: nothing visible */
@@ -73,7 +75,7 @@ typedef struct loong_step_desc {
   int32_t q_chunk[2];     /* causal only: global chunk ids of q rows [0,c) and [c,2c) */
   int32_t kv_chunk[2];    /* causal only: same for the visiting keys */
   int32_t causal;         /* 0: every key visible to every row (chunk fields ignored) */
-  int32_t dtype;          /* LOONG_BF16 | LOONG_FP32 */
+  int32_t dtype;          /* LOONG_BF16 | LOONG_FP32 | LOONG_FP16 */
   float   softmax_scale;  /* multiplies q.k before the softmax (e.g. 1/sqrt(head_dim)) */
   int32_t flags;
   int64_t q_stride[3];    /* batch, head, token strides (elements) of q, o and d_o */
@@ -147,7 +149,8 @@ LOONG_API int loong_bwd_delta(const loong_step_desc* desc, const void* o, const 
 LOONG_API int loong_init_running(int64_t rows, int32_t head_dim, float* out, float* lse, void* stream);
 
 /* Cast the merged fp32 output [rows, head_dim] to the stored activation type
- * (LOONG_BF16: round to nearest even; LOONG_FP32: copy), contiguous. */
+ * (LOONG_BF16, LOONG_FP16: round to nearest even, fp16 overflow gives infinity; LOONG_FP32: copy),
+ * contiguous. */
 LOONG_API int loong_finalize_out(int64_t rows, int32_t head_dim, const float* out, void* o, int32_t dtype,
                        void* stream);
 

@@ -13,7 +13,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libloong.so")
 
 OK, E_NULL, E_SHAPE, E_UNSUPPORTED, E_ALIGN, E_DTYPE, E_HIP = 0, -1, -2, -3, -4, -5, -6
-BF16, FP32 = 0, 1
+BF16, FP32, FP16 = 0, 1, 2
 SKIP, FULL, DIAG = 0, 1, 2
 FUSE_MERGE, ACCUM_DKV, COMPUTE_DELTA, BWD_ONLY_DKV, BWD_ONLY_DQ = 1, 2, 4, 8, 16
 

@@ -16,8 +16,8 @@ int loong_attn_step_fwd(const loong_step_desc* desc, const void* q, const void* 
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
     return fail(LOONG_E_ALIGN, "loong_attn_step_fwd: q/k/v/out must be 16-byte aligned");
   if (desc->batch == 0 || desc->q_len == 0) return LOONG_OK;
-  return desc->dtype == LOONG_BF16 ? launch_fwd_bf16(*desc, g, q, k, v, out, lse, stream)
-                                   : launch_fwd_f32(*desc, g, q, k, v, out, lse, stream);
+  return desc->dtype == LOONG_FP32 ? launch_fwd_f32(*desc, g, q, k, v, out, lse, stream)
+                                   : launch_fwd_bf16(*desc, g, q, k, v, out, lse, stream);
 }
 
 int loong_attn_step_bwd(const loong_step_desc* desc, const void* q, const void* k, const void* v,
@@ -39,9 +39,9 @@ int loong_attn_step_bwd(const loong_step_desc* desc, const void* q, const void* 
   if (desc->batch == 0) return LOONG_OK;
   if (want_delta)
     if (int rc = loong_bwd_delta(desc, o, d_o, delta, stream)) return rc;
-  return desc->dtype == LOONG_BF16
-             ? launch_bwd_bf16(*desc, g, q, k, v, d_o, lse, delta, dq, dk, dv, stream)
-             : launch_bwd_f32(*desc, g, q, k, v, d_o, lse, delta, dq, dk, dv, stream);
+  return desc->dtype == LOONG_FP32
+             ? launch_bwd_f32(*desc, g, q, k, v, d_o, lse, delta, dq, dk, dv, stream)
+             : launch_bwd_bf16(*desc, g, q, k, v, d_o, lse, delta, dq, dk, dv, stream);
 }
 
 }  // extern "C"

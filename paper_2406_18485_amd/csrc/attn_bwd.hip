@@ -1,4 +1,5 @@
-// Backward micro-step on bf16 matrix cores, dK/dV part: gradients of the visiting K/V chunk,
+// Backward micro-step on the 16-bit matrix cores (element class E: bf16 or IEEE half; the text
+// below says bf16 for both), dK/dV part: gradients of the visiting K/V chunk,
 // recomputing the probabilities from the final softmax_lse (paper: Sec. 3.1 last paragraph;
 // Sec. "Selective Checkpoint++").  This step's share of dQ comes from the row-owning pass
 // in attn_bwd_dq.hip, launched right after this kernel.
@@ -73,7 +74,7 @@ struct BwdCfg {
   static_assert(LI >= 1 && LI * 1024 * 4 == QT_B, "tile must split evenly over the staging waves");
 };
 
-template <int D>
+template <class E, int D>
 __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams p) {
   using C = BwdCfg<D>;
   constexpr int BM = C::BM, BN = C::BN, ROWB = C::ROWB, CH = C::CH, LI = C::LI;
@@ -252,12 +253,12 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
             floatx16_t zero;
 #pragma unroll
             for (int v = 0; v < 16; ++v) zero[v] = 0.f;
-            st2[ib] = mfma32(ring[k % (PF + 1)], bfrag[0], zero);
+            st2[ib] = E::mfma(ring[k % (PF + 1)], bfrag[0], zero);
           } else {
-            st2[ib] = mfma32(ring[k % (PF + 1)], bfrag[0], st2[ib]);  // C = delta
+            st2[ib] = E::mfma(ring[k % (PF + 1)], bfrag[0], st2[ib]);  // C = delta
           }
         } else {
-          st2[ib] = mfma32(ring[k % (PF + 1)], bfrag[ks], st2[ib]);
+          st2[ib] = E::mfma(ring[k % (PF + 1)], bfrag[ks], st2[ib]);
         }
         between(kc);
         __builtin_amdgcn_sched_barrier(0);  // keep the operand reads ahead of their use
@@ -279,7 +280,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
         if constexpr (k + PF < 4 * NDB) ring[(k + PF) % (PF + 1)] = operand(k + PF);
         before(kc);
         const bf16x8_t a = as_bf16x8(make_uint4(w2[ib][4 * sl], w2[ib][4 * sl + 1], w2[ib][4 * sl + 2], w2[ib][4 * sl + 3]));
-        acc[db] = mfma32(a, ring[k % (PF + 1)], acc[db]);
+        acc[db] = E::mfma(a, ring[k % (PF + 1)], acc[db]);
         __builtin_amdgcn_sched_barrier(0);
       });
     };
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
       auto exps = [&](int ib, int w) {  // elements 2 w, 2 w + 1 of block ib
         const float p0 = fast_exp2(fmaf(st2[ib][2 * w], p.c, nl[ib][2 * w]));
         const float p1 = fast_exp2(fmaf(st2[ib][2 * w + 1], p.c, nl[ib][2 * w + 1]));
-        w2[ib][w] = pack_bf16x2(p0, p1);
+        w2[ib][w] = E::pack2(p0, p1);
       };
       // S of both blocks; the exponentials of block 0 between the matrix steps of block 1
       rows_product(Qt, [&](auto kc) {
@@ -344,7 +345,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
           pw[ib][4 * hf] = x.x; pw[ib][4 * hf + 1] = x.y; pw[ib][4 * hf + 2] = x.z; pw[ib][4 * hf + 3] = x.w;
         }
       auto etimes = [&](int ib, int w) {  // E = P o T for elements 2 w, 2 w + 1 of block ib
-        w2[ib][w] = pack_bf16x2(bf16_lo(pw[ib][w]) * st2[ib][2 * w], bf16_hi(pw[ib][w]) * st2[ib][2 * w + 1]);
+        w2[ib][w] = E::pack2(E::lo(pw[ib][w]) * st2[ib][2 * w], E::hi(pw[ib][w]) * st2[ib][2 * w + 1]);
       };
 #pragma unroll
       for (int w = 0; w < 8; ++w) etimes(0, w);
@@ -385,7 +386,7 @@ __global__ __launch_bounds__(256) void zero_kernel(int64_t n4, float4* a, float4
   }
 }
 
-template <int D>
+template <class E, int D>
 int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
   constexpr int BM = kBwdBM, BN = kBwdBN;
   // Only key tiles that some query can see are listed (eight equal ranges of the list, one
@@ -424,7 +425,7 @@ int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
     if (int rc = check_launch("loong_attn_step_bwd (clear dk/dv)")) return rc;
   }
   if (total == 0) return LOONG_OK;
-  bwd_dkv_kernel<D><<<dim3(p.map.grid), dim3(kBwdWaves * 64), 0, st>>>(p);
+  bwd_dkv_kernel<E, D><<<dim3(p.map.grid), dim3(kBwdWaves * 64), 0, st>>>(p);
   return check_launch("loong_attn_step_bwd (bf16, dK/dV)");
 }
 
@@ -444,7 +445,9 @@ int launch_bwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bool accumulate = d.flags & LOONG_ACCUM_DKV;
   if (!(d.flags & LOONG_BWD_ONLY_DQ)) {
-    const int rc = d.head_dim == 128 ? launch_d<128>(p, accumulate, st) : launch_d<64>(p, accumulate, st);
+    const int rc = d.dtype == LOONG_FP16
+                       ? (d.head_dim == 128 ? launch_d<Fp16, 128>(p, accumulate, st) : launch_d<Fp16, 64>(p, accumulate, st))
+                       : (d.head_dim == 128 ? launch_d<Bf16, 128>(p, accumulate, st) : launch_d<Bf16, 64>(p, accumulate, st));
     if (rc != LOONG_OK) return rc;
   }
   if (d.flags & LOONG_BWD_ONLY_DKV) return LOONG_OK;

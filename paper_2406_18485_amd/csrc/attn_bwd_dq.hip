@@ -1,4 +1,5 @@
-// dQ pass of the backward micro-step on bf16 matrix cores: this step's share of the
+// dQ pass of the backward micro-step on the 16-bit matrix cores (element class E: bf16 or IEEE
+// half; the text below says bf16 for both): this step's share of the
 // gradient of the local Q chunk, dQ_i += scale * sum_j dS_ij K_j with
 // dS_ij = P_ij (dP_ij - delta_i), P recomputed from the final softmax_lse
 // (paper: Sec. 3.1 last paragraph; Alg. 2 run backwards).
@@ -63,7 +64,7 @@ struct DqCfg {
   static_assert(KI >= 1 && KI * 1024 * kRowWaves == TILE_B, "tile must split evenly over the waves");
 };
 
-template <int D, int KS>
+template <class E, int D, int KS>
 __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
   using C = DqCfg<D, KS>;
   constexpr int NRB = C::NRB, NJB = C::NJB, BNS = C::BNS, TK = C::TK, NBUF = C::NBUF, PD = C::PD, KI = C::KI;
@@ -233,8 +234,8 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
         for (int v = 0; v < 16; ++v) zero[v] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-          s = mfma32(as_bf16x8(*reinterpret_cast<const uint4*>(Kb + row_rd[ks])), qf[ks], ks ? s : zero);
-          dp = mfma32(as_bf16x8(*reinterpret_cast<const uint4*>(Vb + row_rd[ks])), dof[ks], ks ? dp : zero);
+          s = E::mfma(as_bf16x8(*reinterpret_cast<const uint4*>(Kb + row_rd[ks])), qf[ks], ks ? s : zero);
+          dp = E::mfma(as_bf16x8(*reinterpret_cast<const uint4*>(Vb + row_rd[ks])), dof[ks], ks ? dp : zero);
         }
       }
       // ---- dS^T = P^T (dP^T - delta), the softmax scale is applied to the sums at the end
@@ -252,8 +253,8 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
       uint4 pk[2];
 #pragma unroll
       for (int sl = 0; sl < 2; ++sl)
-        pk[sl] = make_uint4(pack_bf16x2(e[8 * sl + 0], e[8 * sl + 1]), pack_bf16x2(e[8 * sl + 2], e[8 * sl + 3]),
-                            pack_bf16x2(e[8 * sl + 4], e[8 * sl + 5]), pack_bf16x2(e[8 * sl + 6], e[8 * sl + 7]));
+        pk[sl] = make_uint4(E::pack2(e[8 * sl + 0], e[8 * sl + 1]), E::pack2(e[8 * sl + 2], e[8 * sl + 3]),
+                            E::pack2(e[8 * sl + 4], e[8 * sl + 5]), E::pack2(e[8 * sl + 6], e[8 * sl + 7]));
       // ---- dQ^T += K^T dS^T.  Element e of the B operand is key 16 sl + 8 (e / 4) + 4 hh + e % 4
       // of the block: the A operand is the run starting at key 16 sl + 4 hh and the run 8 keys on.
 #pragma unroll
@@ -261,7 +262,7 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
           const unsigned char* kp = Kb + sl * 16 * ROWB;
-          acc[db] = mfma32(read_tr_pair(kp + tr_lo[db], kp + tr_hi[db]), as_bf16x8(pk[sl]), acc[db]);
+          acc[db] = E::mfma(read_tr_pair(kp + tr_lo[db], kp + tr_hi[db]), as_bf16x8(pk[sl]), acc[db]);
         }
     }
   }
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
   }
 }
 
-template <int D, int KS>
+template <class E, int D, int KS>
 int launch_cfg(DqParams& p, hipStream_t st) {
   const RowTiling rt = make_row_tiling(p.g, p.G, p.Hq, p.B, kRowWaves / KS, /*list_blind=*/false);
   p.GS = rt.GS; p.ntile[0] = rt.ntile[0]; p.ntile[1] = rt.ntile[1];
@@ -318,8 +319,20 @@ int launch_cfg(DqParams& p, hipStream_t st) {
   if (rt.total_wg == 0) return LOONG_OK;
   if (rt.total_wg > 0x3ffffff0) return fail(LOONG_E_UNSUPPORTED, "backward (dQ) grid too large");
   p.map = make_work_map((int64_t)p.B * rt.hgroups, rt.tiles_total);
-  dq_kernel<D, KS><<<dim3(p.map.grid), dim3(kRowWaves * 64), 0, st>>>(p);
+  dq_kernel<E, D, KS><<<dim3(p.map.grid), dim3(kRowWaves * 64), 0, st>>>(p);
   return check_launch("loong_attn_step_bwd (bf16, dQ)");
+}
+
+template <class E>
+int pick_cfg(DqParams& p, int head_dim, int ks, hipStream_t st) {
+  if (head_dim == 128) {
+    if (ks == 1) return launch_cfg<E, 128, 1>(p, st);
+    if (ks == 2) return launch_cfg<E, 128, 2>(p, st);
+    return launch_cfg<E, 128, 4>(p, st);
+  }
+  if (ks == 1) return launch_cfg<E, 64, 1>(p, st);
+  if (ks == 2) return launch_cfg<E, 64, 2>(p, st);
+  return launch_cfg<E, 64, 4>(p, st);
 }
 
 }  // namespace
@@ -337,14 +350,8 @@ int launch_bwd_dq_bf16(const loong_step_desc& d, const StepGeom& g, const void* 
   hipStream_t st = static_cast<hipStream_t>(stream);
   // LOONG_DQ_KS (1, 2 or 4) overrides the number of key splits (tuning aid)
   const int ks = pick_key_splits(g, p.G, p.Hq, p.B, "LOONG_DQ_KS");
-  if (d.head_dim == 128) {
-    if (ks == 1) return launch_cfg<128, 1>(p, st);
-    if (ks == 2) return launch_cfg<128, 2>(p, st);
-    return launch_cfg<128, 4>(p, st);
-  }
-  if (ks == 1) return launch_cfg<64, 1>(p, st);
-  if (ks == 2) return launch_cfg<64, 2>(p, st);
-  return launch_cfg<64, 4>(p, st);
+  if (d.dtype == LOONG_FP16) return pick_cfg<Fp16>(p, d.head_dim, ks, st);
+  return pick_cfg<Bf16>(p, d.head_dim, ks, st);
 }
 
 }  // namespace loong

@@ -1,4 +1,5 @@
-// Forward micro-step on bf16 matrix cores: Attention(Q, K, V) of Alg. 2 for the local Q
+// Forward micro-step on the 16-bit matrix cores (element class E: bf16 or IEEE half; the text
+// below says bf16 for both): Attention(Q, K, V) of Alg. 2 for the local Q
 // chunk against one visiting K/V chunk, with the Update optionally folded in by starting
 // the online softmax from the running (out, lse).
 //
@@ -77,7 +78,7 @@ struct FwdCfg {
   static_assert(KI >= 1 && KI * 1024 * kFwdWaves == TILE_B, "tile must split evenly over the waves");
 };
 
-template <int D, int KS>
+template <class E, int D, int KS>
 __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) {
   using C = FwdCfg<D, KS>;
   constexpr int NRB = C::NRB, BNS = C::BNS, TK = C::TK, NBUF = C::NBUF, PD = C::PD, KI = C::KI;
@@ -287,7 +288,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
 #pragma unroll
       for (int jb = 0; jb < NJB; ++jb) {
         const uint4 a = *reinterpret_cast<const uint4*>(Kt + jb * 32 * ROWB + k_rd[ks]);
-        s[jb] = mfma32(as_bf16x8(a), qf[ks], s[jb]);
+        s[jb] = E::mfma(as_bf16x8(a), qf[ks], s[jb]);
       }
     // ---- mask (diagonal or ragged end only)
     if (j0 + BNS > klen || (isdiag && j0 + BNS - 1 > wrow0)) {
@@ -330,8 +331,8 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
       }
 #pragma unroll
       for (int sl = 0; sl < 2; ++sl)
-        pk[jb][sl] = make_uint4(pack_bf16x2(e[8 * sl + 0], e[8 * sl + 1]), pack_bf16x2(e[8 * sl + 2], e[8 * sl + 3]),
-                                pack_bf16x2(e[8 * sl + 4], e[8 * sl + 5]), pack_bf16x2(e[8 * sl + 6], e[8 * sl + 7]));
+        pk[jb][sl] = make_uint4(E::pack2(e[8 * sl + 0], e[8 * sl + 1]), E::pack2(e[8 * sl + 2], e[8 * sl + 3]),
+                                E::pack2(e[8 * sl + 4], e[8 * sl + 5]), E::pack2(e[8 * sl + 6], e[8 * sl + 7]));
     }
     // ---- O^T += V^T P^T.  Element e of the B operand is key 16 sl + 8 (e / 4) + 4 hh + e % 4
     // of block jb: the A operand is the run starting at key 16 sl + 4 hh and the run 8 keys on.
@@ -342,7 +343,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
           const unsigned char* vp = Vt + (jb * 32 + sl * 16) * ROWB + v_rd[db];
-          o[db] = mfma32(read_tr_pair(vp, vp + 8 * ROWB), as_bf16x8(pk[jb][sl]), o[db]);
+          o[db] = E::mfma(read_tr_pair(vp, vp + 8 * ROWB), as_bf16x8(pk[jb][sl]), o[db]);
         }
   }
 
@@ -419,7 +420,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
   }
 }
 
-template <int D, int KS>
+template <class E, int D, int KS>
 int launch_cfg(FwdParams& p, hipStream_t st) {
   const RowTiling rt = make_row_tiling(p.g, p.G, p.Hq, p.B, kFwdWaves / KS, /*list_blind=*/!p.fuse);  // unfused: blind rows get the neutral result
   p.GS = rt.GS; p.ntile[0] = rt.ntile[0]; p.ntile[1] = rt.ntile[1];
@@ -428,8 +429,20 @@ int launch_cfg(FwdParams& p, hipStream_t st) {
   if (total == 0) return LOONG_OK;
   if (total > 0x3ffffff0) return fail(LOONG_E_UNSUPPORTED, "forward grid too large");
   p.map = make_work_map((int64_t)p.B * rt.hgroups, rt.tiles_total);
-  fwd_kernel<D, KS><<<dim3(p.map.grid), dim3(kFwdWaves * 64), 0, st>>>(p);
+  fwd_kernel<E, D, KS><<<dim3(p.map.grid), dim3(kFwdWaves * 64), 0, st>>>(p);
   return check_launch("loong_attn_step_fwd (bf16)");
+}
+
+template <class E>
+int pick_cfg(FwdParams& p, int head_dim, int ks, hipStream_t st) {
+  if (head_dim == 128) {
+    if (ks == 1) return launch_cfg<E, 128, 1>(p, st);
+    if (ks == 2) return launch_cfg<E, 128, 2>(p, st);
+    return launch_cfg<E, 128, 4>(p, st);
+  }
+  if (ks == 1) return launch_cfg<E, 64, 1>(p, st);
+  if (ks == 2) return launch_cfg<E, 64, 2>(p, st);
+  return launch_cfg<E, 64, 4>(p, st);
 }
 
 }  // namespace
@@ -445,14 +458,8 @@ int launch_fwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
   hipStream_t st = static_cast<hipStream_t>(stream);
   // LOONG_FWD_KS (1, 2 or 4) overrides the number of key splits (tuning aid)
   const int ks = pick_key_splits(g, p.G, p.Hq, p.B, "LOONG_FWD_KS");
-  if (d.head_dim == 128) {
-    if (ks == 1) return launch_cfg<128, 1>(p, st);
-    if (ks == 2) return launch_cfg<128, 2>(p, st);
-    return launch_cfg<128, 4>(p, st);
-  }
-  if (ks == 1) return launch_cfg<64, 1>(p, st);
-  if (ks == 2) return launch_cfg<64, 2>(p, st);
-  return launch_cfg<64, 4>(p, st);
+  if (d.dtype == LOONG_FP16) return pick_cfg<Fp16>(p, d.head_dim, ks, st);
+  return pick_cfg<Bf16>(p, d.head_dim, ks, st);
 }
 
 }  // namespace loong

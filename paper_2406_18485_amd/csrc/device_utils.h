@@ -5,6 +5,8 @@
 
 #include <type_traits>
 
+#include "loong.h"
+
 namespace loong {
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -37,6 +39,33 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 __device__ __forceinline__ floatx16_t mfma32(bf16x8_t a, bf16x8_t b, floatx16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
+
+// ---- 16-bit storage types.  The kernels keep operand fragments as eight 16-bit lanes in a
+// bf16x8_t whatever the element type is; the element class says how the matrix instruction
+// reads them and how fp32 values are rounded into them (nearest even for both).
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+
+struct Bf16 {
+  static constexpr int code = LOONG_BF16;
+  static __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return pack_bf16x2(lo, hi); }
+  static __device__ __forceinline__ float lo(uint32_t w) { return bf16_lo(w); }
+  static __device__ __forceinline__ float hi(uint32_t w) { return bf16_hi(w); }
+  static __device__ __forceinline__ floatx16_t mfma(bf16x8_t a, bf16x8_t b, floatx16_t c) { return mfma32(a, b, c); }
+};
+
+struct Fp16 {
+  static constexpr int code = LOONG_FP16;
+  static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    floatx2_t f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2_t));
+  }
+  static __device__ __forceinline__ float lo(uint32_t w) { return (float)__builtin_bit_cast(f16x2_t, w)[0]; }
+  static __device__ __forceinline__ float hi(uint32_t w) { return (float)__builtin_bit_cast(f16x2_t, w)[1]; }
+  static __device__ __forceinline__ floatx16_t mfma(bf16x8_t a, bf16x8_t b, floatx16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  }
+};
 
 // Row index inside a 32x32 accumulator block held in register v of a lane of half hh.
 __device__ __forceinline__ constexpr int acc_row(int v, int hh) { return 8 * (v >> 2) + 4 * hh + (v & 3); }

@@ -59,14 +59,14 @@ __global__ __launch_bounds__(kThreads) void init_running_kernel(int64_t n4, int6
   if (i < rows) lse[i] = -INFINITY;
 }
 
-// fp32 -> bf16, eight elements per thread; or plain copy for fp32 storage (four per thread)
-__global__ __launch_bounds__(kThreads) void cast_bf16_kernel(int64_t n8, const float4* __restrict__ in,
+// fp32 -> bf16 or fp16, eight elements per thread; or plain copy for fp32 storage (four per thread)
+template <class E>
+__global__ __launch_bounds__(kThreads) void cast_half_kernel(int64_t n8, const float4* __restrict__ in,
                                                              uint4* __restrict__ o) {
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= n8) return;
   const float4 a = in[2 * i], b = in[2 * i + 1];
-  o[i] = make_uint4(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(b.x, b.y),
-                    pack_bf16x2(b.z, b.w));
+  o[i] = make_uint4(E::pack2(a.x, a.y), E::pack2(a.z, a.w), E::pack2(b.x, b.y), E::pack2(b.z, b.w));
 }
 
 __global__ __launch_bounds__(kThreads) void copy_f32_kernel(int64_t n4, const float4* __restrict__ in,
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kThreads) void copy_f32_kernel(int64_t n4, const fl
 
 // ---- delta_i = sum_k dO_ik O_ik ----------------------------------------------------------
 // LPR lanes per row, each lane 16 bytes at a time; rows are (batch, head, token) with strides.
-template <bool BF16, int LPR>
+template <class E, int LPR>  // E = Bf16, Fp16, or float for fp32 storage
 __global__ __launch_bounds__(kThreads) void delta_kernel(int64_t rows, int heads, int len, int dvec,
                                                          int64_t s0, int64_t s1, int64_t s2,
                                                          const void* __restrict__ o_,
@@ -94,13 +94,13 @@ __global__ __launch_bounds__(kThreads) void delta_kernel(int64_t rows, int heads
   const int64_t base = b * s0 + h * s1 + t * s2;
   float acc = 0.f;
   for (int c = sub; c < dvec; c += LPR) {
-    if (BF16) {
+    if constexpr (!std::is_same<E, float>::value) {
       const uint4 x = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(o_) + base)[c];
       const uint4 y = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(do_) + base)[c];
-      acc += bf16_lo(x.x) * bf16_lo(y.x) + bf16_hi(x.x) * bf16_hi(y.x);
-      acc += bf16_lo(x.y) * bf16_lo(y.y) + bf16_hi(x.y) * bf16_hi(y.y);
-      acc += bf16_lo(x.z) * bf16_lo(y.z) + bf16_hi(x.z) * bf16_hi(y.z);
-      acc += bf16_lo(x.w) * bf16_lo(y.w) + bf16_hi(x.w) * bf16_hi(y.w);
+      acc += E::lo(x.x) * E::lo(y.x) + E::hi(x.x) * E::hi(y.x);
+      acc += E::lo(x.y) * E::lo(y.y) + E::hi(x.y) * E::hi(y.y);
+      acc += E::lo(x.z) * E::lo(y.z) + E::hi(x.z) * E::hi(y.z);
+      acc += E::lo(x.w) * E::lo(y.w) + E::hi(x.w) * E::hi(y.w);
     } else {
       const float4 x = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(o_) + base)[c];
       const float4 y = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(do_) + base)[c];
@@ -174,9 +174,10 @@ int loong_finalize_out(int64_t rows, int32_t head_dim, const float* out, void* o
                        void* stream) {
   clear_error();
   if (!out || !o) return fail(LOONG_E_NULL, "loong_finalize_out: NULL tensor");
-  if (dtype != LOONG_BF16 && dtype != LOONG_FP32) return fail(LOONG_E_DTYPE, "loong_finalize_out: dtype %d", dtype);
+  if (dtype != LOONG_BF16 && dtype != LOONG_FP32 && dtype != LOONG_FP16)
+    return fail(LOONG_E_DTYPE, "loong_finalize_out: dtype %d", dtype);
   if (rows < 0 || head_dim < 1) return fail(LOONG_E_SHAPE, "loong_finalize_out: rows %lld, head_dim %d", (long long)rows, head_dim);
-  const int vec = dtype == LOONG_BF16 ? 8 : 4;
+  const int vec = dtype == LOONG_FP32 ? 4 : 8;
   if (head_dim % vec != 0) return fail(LOONG_E_UNSUPPORTED, "loong_finalize_out: head_dim %d is not a multiple of %d", head_dim, vec);
   if (!aligned16(out) || !aligned16(o)) return fail(LOONG_E_ALIGN, "loong_finalize_out: pointers not 16-byte aligned");
   if (rows > ((int64_t)1 << 40)) return fail(LOONG_E_UNSUPPORTED, "loong_finalize_out: too many rows");
@@ -186,8 +187,11 @@ int loong_finalize_out(int64_t rows, int32_t head_dim, const float* out, void* o
   if (nb > 0x7fffffff) return fail(LOONG_E_UNSUPPORTED, "loong_finalize_out: grid too large");
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (dtype == LOONG_BF16)
-    cast_bf16_kernel<<<dim3((unsigned)nb), dim3(kThreads), 0, st>>>(n, reinterpret_cast<const float4*>(out),
-                                                                   reinterpret_cast<uint4*>(o));
+    cast_half_kernel<Bf16><<<dim3((unsigned)nb), dim3(kThreads), 0, st>>>(n, reinterpret_cast<const float4*>(out),
+                                                                         reinterpret_cast<uint4*>(o));
+  else if (dtype == LOONG_FP16)
+    cast_half_kernel<Fp16><<<dim3((unsigned)nb), dim3(kThreads), 0, st>>>(n, reinterpret_cast<const float4*>(out),
+                                                                         reinterpret_cast<uint4*>(o));
   else
     copy_f32_kernel<<<dim3((unsigned)nb), dim3(kThreads), 0, st>>>(n, reinterpret_cast<const float4*>(out),
                                                                   reinterpret_cast<float4*>(o));
@@ -202,8 +206,7 @@ int loong_bwd_delta(const loong_step_desc* desc, const void* o, const void* d_o,
   if (!aligned16(o) || !aligned16(d_o)) return fail(LOONG_E_ALIGN, "loong_bwd_delta: o/d_o not 16-byte aligned");
   const int64_t rows = (int64_t)desc->batch * desc->n_q_heads * desc->q_len;
   if (rows == 0) return LOONG_OK;
-  const bool bf = desc->dtype == LOONG_BF16;
-  const int dvec = desc->head_dim / (bf ? 8 : 4);
+  const int dvec = desc->head_dim / (desc->dtype == LOONG_FP32 ? 4 : 8);
   const int lpr = pow2_lanes(dvec);
   const int64_t nb = blocks_for(rows, kThreads / lpr);
   if (nb > 0x7fffffff) return fail(LOONG_E_UNSUPPORTED, "loong_bwd_delta: grid too large");
@@ -222,7 +225,7 @@ int loong_bwd_delta(const loong_step_desc* desc, const void* o, const void* d_o,
     case 16: LOONG_DELTA(BF, 16); break; \
     default: LOONG_DELTA(BF, 32); break; \
   }
-  if (bf) { LOONG_DELTA_L(true) } else { LOONG_DELTA_L(false) }
+  if (desc->dtype == LOONG_BF16) { LOONG_DELTA_L(Bf16) } else if (desc->dtype == LOONG_FP16) { LOONG_DELTA_L(Fp16) } else { LOONG_DELTA_L(float) }
 #undef LOONG_DELTA_L
 #undef LOONG_DELTA
   return check_launch("loong_bwd_delta");

@@ -26,8 +26,9 @@ static bool mul_ok(int64_t a, int64_t b, int64_t limit) { return a == 0 || b <= 
 
 int check_step(const loong_step_desc* d, StepGeom* g) {
   if (!d) return fail(LOONG_E_NULL, "descriptor is NULL");
-  if (d->dtype != LOONG_BF16 && d->dtype != LOONG_FP32)
-    return fail(LOONG_E_DTYPE, "dtype %d is neither LOONG_BF16 nor LOONG_FP32", d->dtype);
+  if (d->dtype != LOONG_BF16 && d->dtype != LOONG_FP32 && d->dtype != LOONG_FP16)
+    return fail(LOONG_E_DTYPE, "dtype %d is none of LOONG_BF16, LOONG_FP32, LOONG_FP16", d->dtype);
+  const bool half = d->dtype != LOONG_FP32;  // 16-bit storage: the matrix-core kernels
   if (d->batch < 0 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->head_dim < 1 || d->q_len < 0 ||
       d->kv_len < 0)
     return fail(LOONG_E_SHAPE, "negative size or zero heads (batch %d, heads %d/%d, head_dim %d, q_len %d, kv_len %d)",
@@ -35,16 +36,16 @@ int check_step(const loong_step_desc* d, StepGeom* g) {
   if (d->n_q_heads % d->n_kv_heads != 0)
     return fail(LOONG_E_UNSUPPORTED, "n_q_heads %d is not a multiple of n_kv_heads %d", d->n_q_heads,
                 d->n_kv_heads);
-  if (d->dtype == LOONG_BF16) {
+  if (half) {
     if (d->head_dim != 64 && d->head_dim != 128)
-      return fail(LOONG_E_UNSUPPORTED, "bf16 kernels take head_dim 64 or 128, got %d", d->head_dim);
+      return fail(LOONG_E_UNSUPPORTED, "bf16/fp16 kernels take head_dim 64 or 128, got %d", d->head_dim);
   } else if (d->head_dim > 128 || d->head_dim % 4 != 0) {
     return fail(LOONG_E_UNSUPPORTED, "fp32 kernels take head_dim <= 128 and a multiple of 4, got %d",
                 d->head_dim);
   }
   if (!std::isfinite(d->softmax_scale) || d->softmax_scale <= 0.f)
     return fail(LOONG_E_SHAPE, "softmax_scale must be finite and positive");
-  const int vec = d->dtype == LOONG_BF16 ? 8 : 4;  // elements per 16-byte access
+  const int vec = half ? 8 : 4;  // elements per 16-byte access
   const int64_t* strides[3] = {d->q_stride, d->kv_stride, d->o_stride};
   const int svec[3] = {vec, vec, 4};
   const char* names[3] = {"q_stride", "kv_stride", "o_stride"};

@@ -36,6 +36,7 @@ int check_launch(const char* what);
 }  // namespace loong
 
 // Kernel launchers (defined next to their kernels).  All arguments are already validated.
+// The *_bf16 launchers serve both 16-bit storage types (LOONG_BF16 and LOONG_FP16).
 namespace loong {
 int launch_fwd_f32(const loong_step_desc& d, const StepGeom& g, const void* q, const void* k,
                    const void* v, float* out, float* lse, void* stream);

@@ -23,7 +23,7 @@ class RingShape:
     hkv: int
     d: int
     c: int
-    dtype: int          # B.BF16 | B.FP32
+    dtype: int          # B.BF16 | B.FP32 | B.FP16
     scale: float
     batch: int = 1
 
@@ -57,7 +57,7 @@ class RingReplay:
         self.plan = visit_plan(shape)
         s = shape
         f32 = dict(dtype=torch.float32, device=self.dev)
-        self.store_dtype = torch.bfloat16 if s.dtype == B.BF16 else torch.float32
+        self.store_dtype = {B.BF16: torch.bfloat16, B.FP16: torch.float16, B.FP32: torch.float32}[s.dtype]
         self.rows = s.batch * s.hq * s.L
         self.out = torch.empty(s.batch, s.hq, s.L, s.d, **f32)      # running fp32 output
         self.lse = torch.empty(s.batch, s.hq, s.L, **f32)

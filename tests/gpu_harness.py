@@ -20,12 +20,14 @@ def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
     t = torch.from_numpy(np.ascontiguousarray(x))
     if dtype == "bf16":
         return t.to(torch.bfloat16).to(DEV)   # exact: values are bf16-representable
+    if dtype == "fp16":
+        return t.to(torch.float16).to(DEV)    # exact likewise
     return t.to(DEV)
 
 
 def shape_of(cfg: RingConfig) -> RingShape:
     return RingShape(cp=cfg.cp, w=cfg.w, rank=cfg.rank, hq=cfg.hq, hkv=cfg.hkv, d=cfg.d, c=cfg.c,
-                     dtype=P.BF16 if cfg.dtype == "bf16" else P.FP32, scale=cfg.scale)
+                     dtype={"bf16": P.BF16, "fp16": P.FP16, "fp32": P.FP32}[cfg.dtype], scale=cfg.scale)
 
 
 class Replayed:

@@ -63,16 +63,25 @@ def test_init_running_and_finalize():
     torch.cuda.synchronize()
     assert np.array_equal(o16.float().cpu().numpy(), round_to_bf16(x))   # round to nearest even, bit exact
     assert np.array_equal(o32.cpu().numpy(), x)
+    x[:8, 0] = [65504.0, 65520.0, 6.0e-8, 2.0 ** -25, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, -0.0, 3.0e-5]  # fp16 edges: max, overflow, subnormals, ties
+    h16 = torch.empty(rows, d, dtype=torch.float16, device=DEV)
+    P.finalize_out(rows, d, torch.from_numpy(x).to(DEV), h16, P.FP16)
+    torch.cuda.synchronize()
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16)
+    assert np.array_equal(h16.cpu().numpy().view(np.uint16), want.view(np.uint16))
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 64), ("fp32", 100)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp16", 128), ("fp16", 64), ("fp32", 64), ("fp32", 100)])
 def test_bwd_delta_matches_rowsum(dtype, d):
     b, h, n = 2, 3, 301
     o, do = _f32(b, h, n, d, seed=6), _f32(b, h, n, d, seed=7)
     if dtype == "bf16":
         o, do = round_to_bf16(o), round_to_bf16(do)
+    if dtype == "fp16":
+        o, do = o.astype(np.float16).astype(np.float32), do.astype(np.float16).astype(np.float32)
     desc = P.make_desc(batch=b, n_q_heads=h, n_kv_heads=h, head_dim=d, q_len=n, kv_len=n,
-                       dtype=P.BF16 if dtype == "bf16" else P.FP32, softmax_scale=1.0)
+                       dtype={"bf16": P.BF16, "fp16": P.FP16, "fp32": P.FP32}[dtype], softmax_scale=1.0)
     delta = torch.empty(b, h, n, device=DEV)
     P.bwd_delta(desc, to_dev(o, dtype), to_dev(do, dtype), delta)
     torch.cuda.synchronize()
@@ -143,6 +152,38 @@ def test_bf16_drawn_shapes_full_parity(hq, hkv, d, c, cp, w, rank):
                      d=d, c=c, dtype="bf16", sigma=0.8, seed=5 * c + rank)
     inp = make_inputs(cfg)
     check_full(Replayed(cfg, inp).run(), oracle_full(cfg, inp))
+
+
+# ---- IEEE half storage: the same kernels with the fp16 matrix instruction.  Ten mantissa bits
+# instead of seven: the bounds are those of bf16 cut by four (observed errors are ~8x smaller).
+@pytest.mark.parametrize("hq,hkv,d,c,cp,w,rank", SMALL[2:] + _drawn_shapes(6, seed=16))
+def test_fp16_shapes_full_parity(hq, hkv, d, c, cp, w, rank):
+    cfg = RingConfig(f"half_h{hq}_{hkv}_d{d}_c{c}_cp{cp}w{w}_r{rank}", cp=cp, w=w, rank=rank, hq=hq, hkv=hkv, d=d, c=c,
+                     dtype="fp16", sigma=0.7, seed=300 + c)
+    inp = make_inputs(cfg)
+    ref = oracle_full(cfg, inp)
+    run = Replayed(cfg, inp)
+    check_full(run.run(fuse_merge=True), ref, tol_o=TOL_O / 4, tol_lse=TOL_LSE / 4)
+    check_full(run.run(fuse_merge=False), ref, tol_o=TOL_O / 4, tol_lse=TOL_LSE / 4)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3])
+def test_fp16_shrunken_benchmark_configs_full_parity(idx):
+    import dataclasses
+    cfg = dataclasses.replace(CONFIGS[idx].shrunk(320 if CONFIGS[idx].cp < 16 else 192), dtype="fp16")
+    inp = make_inputs(cfg)
+    check_full(Replayed(cfg, inp).run(), oracle_full(cfg, inp), tol_o=TOL_O / 4, tol_lse=TOL_LSE / 4)
+
+
+def test_fp16_large_scores_stay_finite():
+    """Scores far beyond the fp16 range of exp(): probabilities are formed relative to the running
+    maximum in fp32 and only then rounded to half, so nothing overflows."""
+    cfg = RingConfig("half_large_scores", cp=2, w=2, rank=1, hq=2, hkv=2, d=64, c=96, dtype="fp16", sigma=6.0, seed=41)
+    inp = make_inputs(cfg)
+    ref = oracle_full(cfg, inp)
+    run = Replayed(cfg, inp).run(backward=False)
+    assert np.isfinite(run.out()).all() and np.isfinite(run.lse()).all()
+    check_full(run, ref, tol_o=5e-2, tol_lse=1e-2, backward=False)
 
 
 @pytest.mark.parametrize("idx", [1, 2, 3, 4])

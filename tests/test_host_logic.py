@@ -59,12 +59,15 @@ def _good(**kw):
 def test_validate_accepts_the_benchmark_shapes():
     assert P.validate_step(_good()) == P.OK
     assert P.validate_step(_good(dtype=P.FP32, head_dim=64, n_q_heads=2, n_kv_heads=2, q_len=256, kv_len=256, chunk_len=128)) == P.OK
+    assert P.validate_step(_good(dtype=P.FP16)) == P.OK and P.validate_step(_good(dtype=P.FP16, head_dim=64)) == P.OK
     assert P.validate_step(_good(causal=False, q_len=77, kv_len=0, chunk_len=0)) == P.OK
     assert P.validate_step(_good(batch=0)) == P.OK
 
 
 @pytest.mark.parametrize("kw,code", [
     (dict(dtype=7), P.E_DTYPE),
+    (dict(dtype=3), P.E_DTYPE),
+    (dict(dtype=P.FP16, head_dim=96), P.E_UNSUPPORTED),
     (dict(head_dim=96), P.E_UNSUPPORTED),
     (dict(dtype=P.FP32, head_dim=130), P.E_UNSUPPORTED),
     (dict(dtype=P.FP32, head_dim=256), P.E_UNSUPPORTED),

@@ -26,7 +26,7 @@ class RingConfig:
     hkv: int           # local kv heads
     d: int             # head dim
     c: int             # half-chunk length; local tokens L = 2c, total S = 2*cp*c
-    dtype: str         # "bf16" | "fp32"
+    dtype: str         # "bf16" | "fp16" | "fp32"
     sigma: float       # values ~ N(0,1) * sigma
     seed: int
 
@@ -81,12 +81,14 @@ def bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 def _normal(rng, shape, sigma, dtype):
     x = rng.standard_normal(shape, dtype=np.float32) * np.float32(sigma)
+    if dtype == "fp16":
+        return x.astype(np.float16).astype(np.float32)   # round to nearest even
     return round_to_bf16(x) if dtype == "bf16" else x
 
 
 def make_inputs(cfg: RingConfig) -> dict:
     """q, d_out: the simulated device's rows [hq, L, d]; k_all, v_all: every key of
-    the sequence in natural order [hkv, S, d].  fp32 arrays (bf16-exact for bf16)."""
+    the sequence in natural order [hkv, S, d].  fp32 arrays (bf16- or fp16-exact for the 16-bit types)."""
     rng = np.random.Generator(np.random.Philox(cfg.seed))
     return {
         "q": _normal(rng, (cfg.hq, cfg.L, cfg.d), cfg.sigma, cfg.dtype),
