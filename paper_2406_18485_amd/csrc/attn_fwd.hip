@@ -15,7 +15,9 @@
 // per lane, no registers, no LDS writes by the waves), row-major as in memory, NBUF tiles
 // deep.  Each wave-level load fills 1 KB of LDS contiguously, so the rows cannot be padded;
 // bank conflicts are avoided by permuting which 16-byte piece of a row each lane fetches
-// (an XOR of the piece index with low bits of the row).  K operands are then single
+// (an XOR of the piece index with low bits of the row; the LDS serves 256 bytes per clock,
+// i.e. 16 lanes of a 16-byte read or 32 lanes of a transposing read, and the XORs make each
+// such group touch every bank once).  K operands are then single
 // 16-byte LDS reads; V^T operands are two transposing reads (ds_read_b64_tr_b16), each
 // giving a lane four consecutive keys of one column: exactly the two runs of four keys a
 // lane holds per 16-key slice of the P^T accumulator.
@@ -143,7 +145,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
   const int ld_row = wave * C::RPI + lane / CH;  // row inside the tile for i = 0; later loads add 8*RPI rows
   const int ld_pos = lane % CH;
   const uint32_t k_piece = (uint32_t)(ld_pos ^ ((ld_row / RP) & (CH - 1))) * 16;
-  const uint32_t v_piece = (uint32_t)(ld_pos ^ (((ld_row / RP) & (4 / RP - 1)) * 2)) * 16;
+  const uint32_t v_piece = (uint32_t)(ld_pos ^ (((ld_row / RP) & (4 / RP - 1)) * 4)) * 16;
   const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_t*)smem;  // LDS byte address of the buffers
   auto tile_of = [&](int t, int& kb, int& j0) {
     kb = t < ntk0 ? 0 : 1;
@@ -193,10 +195,12 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
   // V^T operand via transposing reads: in a group of 16 lanes, lane i points at row i / 4
   // of a run of four keys and at columns 4 (i % 4) .. +3 of a 16-column strip; it receives
   // the four keys of column i of the strip.  Lanes 0-31 / 32-63 take runs 4 hh .. 4 hh + 3.
+  // The 32 lanes served in one clock cover four rows x four adjacent pieces (both strips):
+  // the rows' XORs are four pieces apart.
   uint32_t v_rd[NDB];
   {
     const int i16 = lane & 15, r = i16 >> 2, qd = i16 & 3, strip = (lane >> 4) & 1;
-    const int sw = ((r / RP) & (4 / RP - 1)) * 2;
+    const int sw = ((r / RP) & (4 / RP - 1)) * 4;
 #pragma unroll
     for (int db = 0; db < NDB; ++db) {
       const int piece = db * 4 + strip * 2 + (qd >> 1);

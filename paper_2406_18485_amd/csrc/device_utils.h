@@ -117,15 +117,19 @@ __device__ __forceinline__ bf16x8_t read_tr_pair(const unsigned char* lo_run, co
   return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-// XOR applied to the 16-byte piece index of row `row` of an unpadded row-major bf16 tile in
+// XOR applied to the 16-byte piece index of row `row` of an unpadded row-major 16-bit tile in
 // LDS with D columns, chosen so that both access patterns of the kernels are free of bank
-// conflicts: 16 lanes reading the same piece of 16 consecutive rows, and 16 lanes of a
-// transposing read (four consecutive rows x two adjacent pieces).
+// conflicts.  The LDS serves 256 bytes (64 banks) per clock: a 16-byte read takes 16 lanes per
+// clock, which here read the same piece of 16 consecutive rows, so the XOR must differ for
+// all of them; an 8-byte transposing read takes 32 lanes per clock, which here cover four
+// consecutive rows x four adjacent pieces, so the four rows' XORs must differ in the bits
+// above those two (the SQ_LDS_BANK_CONFLICT counter reads zero with this choice; with the
+// four rows only two pieces apart it read half of the transposing reads' cycles).
 template <int D>
 __device__ __forceinline__ constexpr int tile_swizzle(int row) {
-  if (D == 128) return ((row & 3) << 1) | ((row >> 2) & 1) | (((row >> 3) & 1) << 3);
+  if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
   const int m = (row >> 1) & 7;  // D == 64: two rows per 256 bytes
-  return ((m & 1) << 1) | (((m >> 1) & 1) << 2) | ((m >> 2) & 1);
+  return ((m & 1) << 2) | ((m >> 1) & 3);
 }
 
 // f(integral_constant<int, I>) for I = First .. Last - 1, unrolled by instantiation (does not
