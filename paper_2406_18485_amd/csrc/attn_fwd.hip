@@ -281,19 +281,27 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
     const unsigned char* Kt = smem + (t % NBUF) * C::BUF_B + ksp * BNS * ROWB;
     const unsigned char* Vt = smem + (t % NBUF) * C::BUF_B + C::TILE_B + ksp * BNS * ROWB;
 
-    // ---- S^T = K Q^T
+    // ---- S^T = K Q^T.  The K operands are requested PF products ahead (in program order, held
+    // there by the scheduling barriers): left to itself the compiler keeps two reads in flight
+    // and every pair of products then waits out a full LDS latency.
     floatx16_t s[NJB];
+    {
+      constexpr int NIT = NKS * NJB, PF = NIT >= 16 ? 6 : 4;
+      auto k_frag = [&](int it) {
+        return as_bf16x8(*reinterpret_cast<const uint4*>(Kt + (it % NJB) * 32 * ROWB + k_rd[it / NJB]));
+      };
+      bf16x8_t ring[PF + 1];
+      static_for<0, PF>([&](auto i) { ring[i.value] = k_frag(i.value); });
+      floatx16_t zero;
 #pragma unroll
-    for (int jb = 0; jb < NJB; ++jb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) s[jb][v] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks)
-#pragma unroll
-      for (int jb = 0; jb < NJB; ++jb) {
-        const uint4 a = *reinterpret_cast<const uint4*>(Kt + jb * 32 * ROWB + k_rd[ks]);
-        s[jb] = E::mfma(as_bf16x8(a), qf[ks], s[jb]);
-      }
+      for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+      static_for<0, NIT>([&](auto i) {
+        constexpr int it = i.value;
+        if constexpr (it + PF < NIT) ring[(it + PF) % (PF + 1)] = k_frag(it + PF);
+        __builtin_amdgcn_sched_barrier(0);
+        s[it % NJB] = E::mfma(ring[it % (PF + 1)], qf[it / NJB], it < NJB ? zero : s[it % NJB]);
+      });
+    }
     // ---- mask (diagonal or ragged end only)
     if (j0 + BNS > klen || (isdiag && j0 + BNS - 1 > wrow0)) {
 #pragma unroll
