@@ -226,17 +226,28 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
       const unsigned char* Kb = Kt + jb * 32 * ROWB;
       const unsigned char* Vb = Vt + jb * 32 * ROWB;
 
-      // ---- S^T = K Q^T, dP^T = V dO^T (keys x rows: a lane holds one query row)
+      // ---- S^T = K Q^T, dP^T = V dO^T (keys x rows: a lane holds one query row).  The K and V
+      // row operands are requested PF products ahead (in program order, held there by the
+      // scheduling barriers): left to itself the compiler keeps two reads in flight and every
+      // pair of products then waits out a full LDS latency.
       floatx16_t s, dp;
       {
+        constexpr int NIT = 2 * NKS, PF = 6;
+        auto row_frag = [&](int it) {
+          return as_bf16x8(*reinterpret_cast<const uint4*>(((it & 1) ? Vb : Kb) + row_rd[it >> 1]));
+        };
+        bf16x8_t ring[PF + 1];
+        static_for<0, PF>([&](auto i) { ring[i.value] = row_frag(i.value); });
         floatx16_t zero;
 #pragma unroll
         for (int v = 0; v < 16; ++v) zero[v] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-          s = E::mfma(as_bf16x8(*reinterpret_cast<const uint4*>(Kb + row_rd[ks])), qf[ks], ks ? s : zero);
-          dp = E::mfma(as_bf16x8(*reinterpret_cast<const uint4*>(Vb + row_rd[ks])), dof[ks], ks ? dp : zero);
-        }
+        static_for<0, NIT>([&](auto i) {
+          constexpr int it = i.value, ks = it >> 1;
+          if constexpr (it + PF < NIT) ring[(it + PF) % (PF + 1)] = row_frag(it + PF);
+          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (it & 1) dp = E::mfma(ring[it % (PF + 1)], dof[ks], ks ? dp : zero);
+          else s = E::mfma(ring[it % (PF + 1)], qf[ks], ks ? s : zero);
+        });
       }
       // ---- dS^T = P^T (dP^T - delta), the softmax scale is applied to the sums at the end
       float e[16];
