@@ -319,7 +319,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
     for (int jb = 0; jb < NJB; ++jb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[jb][v]);
-    mx = fmaxf(mx, other_half(mx));
+    mx = max_with_other_half(mx);
     const float m_cand = mx * p.c;
     if (__builtin_amdgcn_ballot_w64(m_cand > m_run + kRescaleSlack) != 0) {
       const float m_new = fmaxf(m_run, m_cand);
@@ -394,7 +394,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
       w[sp] = fast_exp2(ms[sp] - m_ref);  // exp2(-inf) = 0
       l_all += ls[sp] * w[sp];
     }
-    const float l_tot = l_all + other_half(l_all);
+    const float l_tot = sum_with_other_half(l_all);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (row_ok) {
 #pragma unroll
@@ -419,7 +419,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
   }
 
   // ---- normalise and store
-  const float l_tot = l_run + other_half(l_run);
+  const float l_tot = sum_with_other_half(l_run);
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   if (row_ok) {
 #pragma unroll

@@ -70,8 +70,19 @@ struct Fp16 {
 // Row index inside a 32x32 accumulator block held in register v of a lane of half hh.
 __device__ __forceinline__ constexpr int acc_row(int v, int hh) { return 8 * (v >> 2) + 4 * hh + (v & 3); }
 
-// Value of the lane 32 places away (wave64).
-__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
+// Maximum / sum of a value with that of the lane 32 places away (wave64), on the vector ALU
+// (v_permlane32_swap: no LDS round trip, and no wait that would also cover the LDS reads in
+// flight).  After the swap one result holds lanes 0-31 of x in both halves, the other lanes
+// 32-63 in both halves; the operations are symmetric, so no selection by half is needed.
+typedef unsigned uintx2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float max_with_other_half(float x) {
+  const uintx2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_with_other_half(float x) {
+  const uintx2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
 // ---- global memory -> LDS without registers -------------------------------------------------
 // 16 (or 4) bytes per lane from global memory straight into LDS: lane l's data lands at
