@@ -8,8 +8,12 @@ every K/V chunk resident in HBM, launches back to back on one stream.
 Prints ONE JSON line: fwd+bwd TFLOP/s (14*d FLOP per visible (query, key) pair per q
 head: 4d forward, 10d backward including the recomputation the method needs), the MFMA
 roofline of the dominant kernel (the dK/dV kernel of the backward step, timed with events
-around each launch), and the fp64 oracle timed on the host cores on a bounded sample of the
-same workload.
+around a rotating sample of its launches inside the timed region: every event costs a few
+microseconds of stream time, so bracketing all launches would slow the pass by ~4 %), and
+the fp64 oracle timed on the host cores on a bounded sample of the same workload.  Extras,
+measured after the timed region: every kernel bracketed, the pass replayed from a captured
+graph, the step classes, Update alone, the two-buffer replay, the layout steps, the matrix
+cores alone.
 """
 from __future__ import annotations
 
@@ -108,66 +112,125 @@ def main():
     rep, s = run.rep, run.rep.shape
     fuse = not args.unfused
 
-    def one_pass(ev=None):
-        if ev:
-            ev["fwd0"].record()
+    desc0 = P.make_desc(batch=1, n_q_heads=s.hq, n_kv_heads=s.hkv, head_dim=s.d, q_len=s.L, kv_len=s.L,
+                        dtype=s.dtype, softmax_scale=s.scale)
+    step_desc = [P.make_desc(batch=1, n_q_heads=s.hq, n_kv_heads=s.hkv, head_dim=s.d, q_len=s.L, kv_len=s.L,
+                             dtype=s.dtype, softmax_scale=s.scale, causal=True, chunk_len=s.c,
+                             q_chunk=st["q_chunk"], kv_chunk=st["kv_chunk"]) for st in rep.plan]
+    E = lambda: torch.cuda.Event(enable_timing=True)
+
+    def backward_step(i, flags):
+        src = rep.plan[i]["src_rank"]
+        d = step_desc[i]
+        d.flags = flags
+        P.attn_step_bwd(d, run.q, run.k_by_src[src], run.v_by_src[src], None, run.d_o, rep.lse, rep.delta,
+                        None if flags & P.BWD_ONLY_DKV else rep.dq,
+                        None if flags & P.BWD_ONLY_DQ else rep.dk[src], None if flags & P.BWD_ONLY_DQ else rep.dv[src])
+
+    def one_pass(sampled=(), every=None):
+        """One pass of the path.  `sampled`: {step: (ev0, ev1)} brackets the dK/dV kernel of those
+        backward micro-steps with events (the step is then issued as its two halves); `every`: an event
+        dictionary that brackets the forward replay and both halves of every backward micro-step."""
+        if every:
+            every["fwd0"].record()
         rep.forward(run.q, run.k_by_src, run.v_by_src, fuse_merge=fuse)
-        if ev:
-            ev["fwd1"].record()
-        desc0 = P.make_desc(batch=1, n_q_heads=s.hq, n_kv_heads=s.hkv, head_dim=s.d, q_len=s.L, kv_len=s.L,
-                            dtype=s.dtype, softmax_scale=s.scale)
+        if every:
+            every["fwd1"].record()
         P.bwd_delta(desc0, rep.o, run.d_o, rep.delta)
         rep.dq.zero_()
-        for i, step in enumerate(rep.plan):
-            src = step["src_rank"]
-            d = P.make_desc(batch=1, n_q_heads=s.hq, n_kv_heads=s.hkv, head_dim=s.d, q_len=s.L, kv_len=s.L,
-                            dtype=s.dtype, softmax_scale=s.scale, causal=True, chunk_len=s.c,
-                            q_chunk=step["q_chunk"], kv_chunk=step["kv_chunk"])
-            # the backward micro-step is two kernels; issued one by one so that each can be timed
-            if ev:
-                ev["bwd"][i][0].record()
-            d.flags = P.BWD_ONLY_DKV
-            P.attn_step_bwd(d, run.q, run.k_by_src[src], run.v_by_src[src], None, run.d_o, rep.lse, rep.delta,
-                            None, rep.dk[src], rep.dv[src])
-            if ev:
-                ev["bwd"][i][1].record()
-            d.flags = P.BWD_ONLY_DQ
-            P.attn_step_bwd(d, run.q, run.k_by_src[src], run.v_by_src[src], None, run.d_o, rep.lse, rep.delta,
-                            rep.dq, None, None)
-            if ev:
-                ev["bwd"][i][2].record()
+        for i in range(cfg.cp):
+            if every:
+                every["bwd"][i][0].record()
+                backward_step(i, P.BWD_ONLY_DKV)
+                every["bwd"][i][1].record()
+                backward_step(i, P.BWD_ONLY_DQ)
+                every["bwd"][i][2].record()
+            elif i in sampled:
+                sampled[i][0].record()
+                backward_step(i, P.BWD_ONLY_DKV)
+                sampled[i][1].record()
+                backward_step(i, P.BWD_ONLY_DQ)
+            else:
+                backward_step(i, 0)
 
-    def new_events():
-        E = lambda: torch.cuda.Event(enable_timing=True)
-        return {"fwd0": E(), "fwd1": E(), "bwd": [(E(), E(), E()) for _ in rep.plan]}
+    # Every event costs a gap of a few microseconds on the stream, so the timed region brackets only
+    # the dominant kernel, and only on a rotating sample of the micro-steps: pass p times the
+    # dK/dV kernel of the steps i with i = p (mod max(steps, cp)) folded onto the steps, so that every step
+    # is sampled equally often (when steps is a multiple of cp, or smaller than cp).
+    def sample_of(pass_no):
+        if args.steps >= cfg.cp:
+            return [pass_no % cfg.cp]
+        return [i for i in range(cfg.cp) if i % args.steps == pass_no % args.steps]
 
     for _ in range(args.warmup):
         one_pass()
     torch.cuda.synchronize()
-    events = [new_events() for _ in range(args.steps)]
+    samples = [{i: (E(), E()) for i in sample_of(pno)} for pno in range(args.steps)]
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        one_pass(events[i])
+    for pno in range(args.steps):
+        one_pass(sampled=samples[pno])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
     ms_per_step = dt / args.steps * 1e3
     pairs = pairs_per_head(cfg) * cfg.hq
     tflops = 14.0 * cfg.d * pairs / (dt / args.steps) / 1e12
-    fwd_ms = sum(e["fwd0"].elapsed_time(e["fwd1"]) for e in events) / args.steps
-    dkv_ms = sum(a.elapsed_time(b) for e in events for a, b, _ in e["bwd"]) / args.steps
-    dq_ms = sum(b.elapsed_time(c) for e in events for _, b, c in e["bwd"]) / args.steps
-    bwd_ms = dkv_ms + dq_ms
-    # dominant kernel: the dK/dV kernel of the backward micro-step.  Its algorithmic work is
-    # four of the backward's five matrix products (S, dP, dV, dK): 8*d FLOP per visible pair.
+    # dominant kernel: the dK/dV kernel of the backward micro-step.  Its algorithmic work is four of
+    # the backward's five matrix products (S, dP, dV, dK): 8*d FLOP per visible pair.  Average launch
+    # duration: mean over the micro-steps of the mean of each step's samples.
+    per_step = {}
+    for smp in samples:
+        for i, (a, b) in smp.items():
+            per_step.setdefault(i, []).append(a.elapsed_time(b))
+    assert len(per_step) == cfg.cp, "every micro-step must have been sampled"
+    dkv_launch_ms = sum(sum(v) / len(v) for v in per_step.values()) / cfg.cp
+    dkv_ms = dkv_launch_ms * cfg.cp
     dkv_tflops = 8.0 * cfg.d * pairs / (dkv_ms * 1e-3) / 1e12
+
+    # ---- every kernel bracketed (costs ~4 % of the pass: measured outside the timed region) ----------
+    def new_events():
+        return {"fwd0": E(), "fwd1": E(), "bwd": [(E(), E(), E()) for _ in rep.plan]}
+    n_inst = 3
+    events = [new_events() for _ in range(n_inst)]
+    t1 = time.perf_counter()
+    for ev in events:
+        one_pass(every=ev)
+    torch.cuda.synchronize()
+    instrumented_ms = (time.perf_counter() - t1) / n_inst * 1e3
+    fwd_ms = sum(e["fwd0"].elapsed_time(e["fwd1"]) for e in events) / n_inst
+    dkv_all_ms = sum(a.elapsed_time(b) for e in events for a, b, _ in e["bwd"]) / n_inst
+    dq_ms = sum(b.elapsed_time(c) for e in events for _, b, c in e["bwd"]) / n_inst
+    bwd_ms = dkv_all_ms + dq_ms
     per_kernel = {
+        "note": f"every launch bracketed with events in {n_inst} extra passes after the timed region "
+                f"({round(instrumented_ms, 4)} ms per such pass)",
         "fwd_kernel": {"flop_per_pair": "4*d", "avg_launch_ms": round(fwd_ms / cfg.cp, 4),
                        "tflops": round(4.0 * cfg.d * pairs / (fwd_ms * 1e-3) / 1e12, 1)},
-        "bwd_dkv_kernel": {"flop_per_pair": "8*d", "avg_launch_ms": round(dkv_ms / cfg.cp, 4), "tflops": round(dkv_tflops, 1)},
+        "bwd_dkv_kernel": {"flop_per_pair": "8*d", "avg_launch_ms": round(dkv_all_ms / cfg.cp, 4),
+                           "tflops": round(8.0 * cfg.d * pairs / (dkv_all_ms * 1e-3) / 1e12, 1)},
         "dq_kernel": {"flop_per_pair": "6*d (S and dP recomputed)", "avg_launch_ms": round(dq_ms / cfg.cp, 4),
                       "tflops": round(6.0 * cfg.d * pairs / (dq_ms * 1e-3) / 1e12, 1)},
     }
+    # the same pass replayed from a captured graph (no host launches; extra, never `value`)
+    graph_ms = None
+    try:
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            one_pass()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                one_pass()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = round((time.perf_counter() - t2) / args.steps * 1e3, 4)
+    except Exception as exc:  # a capture failure must not cost the benchmark line
+        graph_ms = f"capture failed: {exc}"
     # ---- extra figures, measured after the timed region ------------------------------------
     def timed(fn, reps):
         fn()
@@ -186,7 +249,7 @@ def main():
         if not idx:
             return None
         tot = sum(e["bwd"][i][0].elapsed_time(e["bwd"][i][2]) for e in events for i in idx)
-        return round(tot / (len(idx) * args.steps), 4)
+        return round(tot / (len(idx) * n_inst), 4)
     step_classes = {"bwd_ms_diagonal_step": cls_ms(lambda st: st["src_rank"] == cfg.rank),
                     "bwd_ms_other_steps": cls_ms(lambda st: st["src_rank"] != cfg.rank)}
     # Update as a kernel of its own (HBM-bound): 3 x 4 x d + 3 x 4 bytes per merged row
@@ -251,9 +314,11 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "bwd_dkv_kernel (dK/dV half of one backward micro-step)",
                      "achieved": round(dkv_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(dkv_tflops / PEAK_BF16_TFLOPS, 4), "traffic": TRAFFIC.get(cfg.name),
-                     "avg_launch_ms": round(dkv_ms / cfg.cp, 4), "launches_per_step": cfg.cp,
+                     "avg_launch_ms": round(dkv_launch_ms, 4), "launches_per_step": cfg.cp,
+                     "timed_launches": sum(len(v) for v in per_step.values()),
                      "flop_per_launch": round(8.0 * cfg.d * pairs / cfg.cp)},
         "kernels": per_kernel,
+        "graph_replay_ms_per_step": graph_ms,
         "step_classes": step_classes,
         "merge_only": merge,
         "layout_steps": layout,

@@ -231,6 +231,44 @@ def test_two_buffer_forward_equals_the_resident_replay(idx, c):
         assert torch.equal(run.rep.out, ref[0]) and torch.equal(run.rep.lse, ref[1]) and torch.equal(run.rep.o, ref[2])
 
 
+@pytest.mark.parametrize("idx,c", [(1, 256), (3, 192)])
+def test_captured_graph_of_the_whole_pass_replays_bit_exactly(idx, c):
+    """The launch sequence of a forward + backward pass (no allocation, no host synchronisation, no
+    memset node: clears are fill kernels) can be captured in a HIP graph.  Every replay, with eager work of
+    the program's own and synchronisations in between, must reproduce the eager results bit for bit (shapes
+    without split dK/dV loops, so no atomics are involved)."""
+    cfg = CONFIGS[idx].shrunk(c)
+    run = Replayed(cfg, make_inputs(cfg))
+    rep = run.rep
+
+    def one_pass():
+        rep.forward(run.q, run.k_by_src, run.v_by_src)
+        rep.backward(run.q, run.k_by_src, run.v_by_src, run.d_o)
+
+    one_pass()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (rep.out, rep.lse, rep.o, rep.dq)]
+    ref_dk, ref_dv = rep.dk.clone(), rep.dv.clone()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        one_pass()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            one_pass()
+    torch.cuda.synchronize()
+    for i in range(3):
+        for t in (rep.out, rep.o, rep.dq, rep.dk, rep.dv):   # eager work between the replays
+            t.fill_(float(i + 3))
+        rep.lse.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((rep.out, rep.lse, rep.o, rep.dq), ref):
+            assert torch.equal(got, want), f"replay {i}"
+        assert torch.allclose(rep.dk, ref_dk, atol=1e-3, rtol=0) and torch.allclose(rep.dv, ref_dv, atol=1e-3, rtol=0)
+
+
 # ------------------------------------------------------------------------------ direct calls, edge cases
 def _direct(dtype, b, hq, hkv, d, nq, nk, seed, strided=False, accum=False):
     rng = np.random.default_rng(seed)
