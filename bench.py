@@ -71,8 +71,8 @@ def cpu_baseline(cfg, inp, budget_rows: int):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=48)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=1, help="index into workloads.CONFIGS (1 = 7B MHA shard, 32K)")
     ap.add_argument("--cpu-rows", type=int, default=-1,
                     help="rows of the oracle sample (0: skip the CPU baseline; -1: sized for about 15 s of host work)")

@@ -72,14 +72,18 @@ class RingReplay:
     # ---- forward: cp x (Attention [+ Update]) then the cast to the stored activation type
     def forward(self, q, k_by_src, v_by_src, fuse_merge=True, stream=None):
         s = self.shape
-        B.init_running(self.rows, s.d, self.out, self.lse, stream)
-        if not fuse_merge and self.block_out is None:
-            self.block_out = torch.empty_like(self.out)
-            self.block_lse = torch.empty_like(self.lse)
-        for step in self.plan:
+        if not fuse_merge:
+            B.init_running(self.rows, s.d, self.out, self.lse, stream)
+            if self.block_out is None:
+                self.block_out = torch.empty_like(self.out)
+                self.block_lse = torch.empty_like(self.lse)
+        for t, step in enumerate(self.plan):
             src = step["src_rank"]
             if fuse_merge:
-                B.attn_step_fwd(_desc(s, step, B.FUSE_MERGE), q, k_by_src[src], v_by_src[src], self.out, self.lse, stream)
+                # the first visit writes the running result (rows that see nothing get the neutral
+                # element), the later ones merge into it: no separate initialisation
+                B.attn_step_fwd(_desc(s, step, B.FUSE_MERGE if t else 0), q, k_by_src[src], v_by_src[src],
+                                self.out, self.lse, stream)
             else:
                 B.attn_step_fwd(_desc(s, step, 0), q, k_by_src[src], v_by_src[src], self.block_out, self.block_lse, stream)
                 B.lse_merge(self.rows, s.d, self.out, self.lse, self.block_out, self.block_lse, stream)
@@ -122,7 +126,6 @@ class RingReplay:
                 bufs[b][1].copy_(v_by_src[src], non_blocking=True)
                 filled[b].record(stream)
 
-        B.init_running(self.rows, s.d, self.out, self.lse)
         for ev in released:
             ev.record(main)
         cur, nxt, out = 0, 1, 2
@@ -135,7 +138,7 @@ class RingReplay:
             if b + 1 < s.w:
                 receive(inner, nxt, self.plan[t + 1]["src_rank"])
             main.wait_event(filled[cur])
-            B.attn_step_fwd(_desc(s, step, B.FUSE_MERGE), q, bufs[cur][0], bufs[cur][1], self.out, self.lse)
+            B.attn_step_fwd(_desc(s, step, B.FUSE_MERGE if t else 0), q, bufs[cur][0], bufs[cur][1], self.out, self.lse)
             released[cur].record(main)
             if b + 1 < s.w:
                 cur, nxt = nxt, cur
