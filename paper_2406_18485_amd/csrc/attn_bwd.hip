@@ -49,10 +49,10 @@ struct BwdParams {
   int64_t qs[3], ks[3];
   StepGeom g;
   float scale, c;  // softmax scale; scale * log2(e)
-  // per key segment: key tiles, workgroups sharing the query loop of one key tile, and whether
-  // dk/dv are added to with atomics (accumulate flag, or a shared query loop)
-  int nkt[2], ns[2], add[2];
-  WorkMap map;     // units = batch x kv heads, items = (key tile, split) pairs of both segments
+  int add_dkv;     // 1: dk/dv are added to with atomics (accumulate flag or split iteration space)
+  int nkt[2], kt_total;
+  int nsplit;
+  WorkMap map;     // units = batch x kv heads, items = key tiles x splits
 };
 
 constexpr int kBwdWaves = 8;            // 4 key groups x {P wave, E wave}
@@ -85,20 +85,10 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
   // ---- which (batch, kv head, key tile, split)
   int bhk, rem;  // key tiles in storage order see ever fewer queries: that is the ranking
   if (!decode_work(p.map, blockIdx.x, bhk, rem)) return;
-  // The (key tile, split) items of the two key segments are dealt in proportion, so that the
-  // ranking stays "longest query loop first" when both segments run from long to short
-  // loops (a step with diagonal blocks): item `rem` is the next one of segment 1 whenever
-  // the running share of segment 1 crosses an integer.
-  const int items0 = p.nkt[0] * p.ns[0], items1 = p.nkt[1] * p.ns[1];
-  const int before1 = (int)((int64_t)rem * items1 / (items0 + items1));        // items of segment 1 before this one
-  const int upto1 = (int)((int64_t)(rem + 1) * items1 / (items0 + items1));
-  const int kb = upto1 > before1 ? 1 : 0;
-  const int nsp = kb ? p.ns[1] : p.ns[0];
-  const int in_seg = kb ? before1 : rem - before1;
-  const int kt = in_seg / nsp, sp = in_seg - kt * nsp;  // key tile inside its segment, split
-  const bool add_dkv = kb ? p.add[1] : p.add[0];
+  const int kt = rem / p.nsplit, sp = rem - kt * p.nsplit;
   const int b = bhk / p.Hkv, hk = bhk - b * p.Hkv;
-  const int koff0 = kt * BN;
+  const int kb = kt >= p.nkt[0] ? 1 : 0;
+  const int koff0 = (kb ? kt - p.nkt[0] : kt) * BN;
   const Segment kseg = kb ? p.g.k[1] : p.g.k[0];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hh = lane >> 5;
@@ -121,8 +111,8 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
   const int cnt1 = clsq1 == LOONG_SKIP ? 0 : nt1 - first1;
   const int per_g = cnt0 + cnt1;
   const int n_it = per_g * p.G;
-  const int it_begin = (int)((int64_t)n_it * sp / nsp);
-  const int it_end = (int)((int64_t)n_it * (sp + 1) / nsp);
+  const int it_begin = (int)((int64_t)n_it * sp / p.nsplit);
+  const int it_end = (int)((int64_t)n_it * (sp + 1) / p.nsplit);
   // iteration -> (head of the group, tile inside the group's list); advanced without divisions
   struct Cursor { int gq, r; };
   auto advance = [&](Cursor& cu) {
@@ -382,7 +372,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
       const int koff = koff0 + 32 * kg + acc_row(v, hh);
       if (koff < kseg.len) {
         const int64_t o = (int64_t)koff * D + db * 32;
-        if (add_dkv) unsafeAtomicAdd(base + o, acc[db][v] * f);
+        if (p.add_dkv) unsafeAtomicAdd(base + o, acc[db][v] * f);
         else base[o] = acc[db][v] * f;
       }
     }
@@ -401,45 +391,34 @@ int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
   constexpr int BM = kBwdBM, BN = kBwdBN;
   // Only key tiles that some query can see are listed (eight equal ranges of the list, one
   // per XCD, then carry equal work); key segments nobody sees are cleared by the zero pass.
-  // Per key segment: the longest query loop of one of its key tiles and the sum of the loops
-  // of all of them, in query tiles (a DIAG block's key tile j starts at query tile j * BN / BM).
-  bool unseen_keys = false;
-  int64_t longest[2] = {0, 0}, sum[2] = {0, 0};
+  // The query-tile loop is spread over several workgroups when the listed tiles are fewer
+  // than the CUs, and once more when a diagonal block makes their loop lengths uneven.
+  p.kt_total = 0;
+  bool diag = false, unseen_keys = false;
   for (int kb = 0; kb < 2; ++kb) {
-    p.nkt[kb] = 0;
-    if (kb >= p.g.nk) continue;
-    const int64_t nkt = (p.g.k[kb].len + BN - 1) / BN;
-    for (int a = 0; a < p.g.nq; ++a) {
-      const int64_t nt = (p.g.q[a].len + BM - 1) / BM;
-      if (p.g.cls[a][kb] == LOONG_SKIP || nt == 0) continue;
-      longest[kb] += nt;
-      for (int64_t j = 0; j < nkt; ++j)
-        sum[kb] += p.g.cls[a][kb] == LOONG_DIAG ? std::max<int64_t>(nt - j * BN / BM, 0) : nt;
-    }
-    longest[kb] *= p.G;
-    sum[kb] *= p.G;
-    if (longest[kb] > 0) p.nkt[kb] = (int)nkt;
-    unseen_keys |= longest[kb] == 0 && p.g.k[kb].len > 0;
+    bool seen = false;
+    if (kb < p.g.nk)
+      for (int a = 0; a < p.g.nq; ++a) {
+        seen |= p.g.cls[a][kb] != LOONG_SKIP && p.g.q[a].len > 0;
+        diag |= p.g.cls[a][kb] == LOONG_DIAG;
+      }
+    p.nkt[kb] = seen ? (p.g.k[kb].len + BN - 1) / BN : 0;
+    p.kt_total += p.nkt[kb];
+    unseen_keys |= kb < p.g.nk && !seen && p.g.k[kb].len > 0;
   }
-  // A workgroup per key tile when that fills the chip evenly; else the query loops of a
-  // segment's key tiles are shared by several workgroups (fp32 atomics on that segment's
-  // dk/dv), as many as bring its longest loop down to a CU's share of the whole step.  The
-  // two segments of a step with a diagonal block differ: its early keys see up to twice as
-  // many queries as its late ones, and only they are split.
-  const int64_t share = std::max<int64_t>((sum[0] + sum[1]) * p.Hkv * p.B / 256, 1);
-  bool split = false;
-  int64_t items = 0;
-  for (int kb = 0; kb < 2; ++kb) {
-    const int64_t want = (longest[kb] + share - 1) / share;
-    p.ns[kb] = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, 16), longest[kb]));
-    p.add[kb] = (accumulate || p.ns[kb] > 1) ? 1 : 0;
-    split |= p.nkt[kb] > 0 && p.ns[kb] > 1;
-    items += (int64_t)p.nkt[kb] * p.ns[kb];
-  }
-  const int64_t total = items * p.Hkv * p.B;
+  const int64_t base = (int64_t)p.kt_total * p.Hkv * p.B;
+  const int64_t busy = base;
+  int nsplit = 1;
+  const int64_t q_tiles = std::max<int64_t>((int64_t)p.G * ((p.q_len + BM - 1) / BM), 1);
+  if (busy > 0 && busy < 256) nsplit = (int)std::min<int64_t>((256 + busy - 1) / busy, 16);
+  if (diag && busy * nsplit <= 512) nsplit *= 2;
+  nsplit = (int)std::min<int64_t>(nsplit, q_tiles);
+  p.nsplit = nsplit;
+  p.add_dkv = (accumulate || nsplit > 1) ? 1 : 0;
+  const int64_t total = base * nsplit;
   if (total > 0x3ffffff0) return fail(LOONG_E_UNSUPPORTED, "backward grid too large");
-  p.map = make_work_map((int64_t)p.Hkv * p.B, items);
-  if ((split || unseen_keys) && !accumulate) {
+  p.map = make_work_map((int64_t)p.Hkv * p.B, (int64_t)p.kt_total * nsplit);
+  if ((nsplit > 1 || unseen_keys) && !accumulate) {
     const int64_t n4 = (int64_t)p.B * p.Hkv * p.kv_len * D / 4;
     zero_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st>>>(n4, reinterpret_cast<float4*>(p.dk),
                                                                           reinterpret_cast<float4*>(p.dv));
