@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=-1,
                     help="rows of the oracle sample (0: skip the CPU baseline; -1: sized for about 15 s of host work)")
     ap.add_argument("--unfused", action="store_true", help="run Attention and Update as separate kernels")
+    ap.add_argument("--rank", type=int, default=None,
+                    help="simulated rank of the ring (default: the workload's, rank 0); later ranks see more "
+                         "steps in which both local chunks attend the visiting chunk's early half")
     ap.add_argument("--dtype", choices=["bf16", "fp16"], default=None,
                     help="storage type of q, k, v, o, d_o (default: the workload's, bf16); fp16 runs the same kernels "
                          "with the fp16 matrix instruction (same 2.5 PFLOP/s peak)")
@@ -93,6 +96,10 @@ def main():
     from workloads import CONFIGS, make_inputs
 
     cfg = CONFIGS[args.config]
+    if args.rank is not None:
+        if not 0 <= args.rank < cfg.cp:
+            sys.exit(f"--rank must be in [0, {cfg.cp})")
+        cfg = cfg.on_rank(args.rank)
     if args.dtype and cfg.dtype != "fp32":
         import dataclasses
         cfg = dataclasses.replace(cfg, dtype=args.dtype)
