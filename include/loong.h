@@ -132,8 +132,15 @@ LOONG_API int loong_lse_merge(int64_t rows, int32_t head_dim, float* out, float*
  * Outputs: dq [B,Hq,q_len,d] fp32 (o_stride) is ADDED to (zero it before the first
  * step); every row is updated by one thread group in a fixed order, so dq is
  * bit-reproducible.  dk, dv fp32 contiguous [B,Hkv,kv_len,d] are overwritten, or added to
- * with LOONG_ACCUM_DKV (then, and when a step has too few key tiles to fill the chip and
- * its query loop is split, they are accumulated with fp32 atomics in no fixed order).
+ * with LOONG_ACCUM_DKV (a plain read-modify-write: two calls that add into the same dk, dv
+ * must be ordered).  dk, dv are bit-reproducible too: when a step has too few key tiles to
+ * fill the chip, several workgroups share a key tile's query loop and the last one to
+ * arrive adds their partial sums in a fixed order.  Those partial sums live in a block of
+ * device memory the library owns (one per device, allocated on first use, grown on demand,
+ * up to about 64 MiB): calls that use it on one device must be ordered on one stream, and
+ * a call that has to allocate or grow it synchronises the device and fails under stream
+ * capture (LOONG_E_HIP) - run the step once eagerly, or call loong_reserve_workspace,
+ * before capturing.  The bf16/fp16 kernels only; the fp32 kernels need no such block.
  * The two halves run as two kernels on `stream`; LOONG_BWD_ONLY_DKV / LOONG_BWD_ONLY_DQ
  * run one of them (both flags together: LOONG_E_UNSUPPORTED).
  */
@@ -153,6 +160,10 @@ LOONG_API int loong_init_running(int64_t rows, int32_t head_dim, float* out, flo
  * contiguous. */
 LOONG_API int loong_finalize_out(int64_t rows, int32_t head_dim, const float* out, void* o, int32_t dtype,
                        void* stream);
+
+/* Make the library's block for partial results on the current device at least `bytes`
+ * large now (host-synchronous; see loong_attn_step_bwd). */
+LOONG_API int loong_reserve_workspace(int64_t bytes);
 
 /* Validate a descriptor exactly as the step calls do, without touching a device. */
 LOONG_API int loong_validate_step(const loong_step_desc* desc);

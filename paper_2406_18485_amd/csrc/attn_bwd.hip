@@ -49,9 +49,11 @@ struct BwdParams {
   int64_t qs[3], ks[3];
   StepGeom g;
   float scale, c;  // softmax scale; scale * log2(e)
-  int add_dkv;     // 1: dk/dv are added to with atomics (accumulate flag or split iteration space)
+  int accumulate;  // 1: the results are added to dk/dv instead of stored
   int nkt[2], kt_total;
-  int nsplit;
+  int nsplit;      // workgroups that share the query loop of one key tile
+  uint32_t* ws_cnt;  // nsplit > 1: arrival counter per (batch, kv head, key tile), zero between launches
+  float* ws_part;    // nsplit > 1: partial dK/dV of every (key tile, split), in accumulator layout
   WorkMap map;     // units = batch x kv heads, items = key tiles x splits
 };
 
@@ -361,8 +363,56 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
     st_e = st_p; st_p = st_n; st_n = freed;
   }
 
+  // ---- several workgroups shared this key tile's query loop: each parks its partial sums
+  // in the library's workspace, and the one that arrives last adds them up in split order,
+  // so the result does not depend on the order of arrival (no atomics on dK/dV).
+  // The partials cross between XCDs, whose L2s are not coherent for ordinary accesses.  A
+  // device-scope fence would do (release: write back the XCD's L2, acquire: invalidate it),
+  // but every workgroup would pay for the whole cache (measured: 1.4-1.8x the step time).
+  // Instead every partial word is stored and loaded as a relaxed device-scope atomic, i.e.
+  // written through to and read from the level all XCDs share; the stores are waited for
+  // (vmcnt) before the workgroup's arrival is counted, and the last workgroup's loads are
+  // issued after its count has returned.
+  if (p.nsplit > 1) {
+    __shared__ int s_last;
+    const int tile_id = bhk * p.kt_total + kt;
+    constexpr int WAVE_F = NDB * 16 * 64;  // floats per wave and slot
+    float* parts = p.ws_part + (int64_t)tile_id * p.nsplit * (kBwdWaves * WAVE_F) + wave * WAVE_F + lane;
+    {
+      float* mine = parts + (int64_t)sp * (kBwdWaves * WAVE_F);
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          __hip_atomic_store(mine + (db * 16 + v) * 64, acc[db][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (tid == 0) {
+      const uint32_t before = __hip_atomic_fetch_add(p.ws_cnt + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_last = before == (uint32_t)p.nsplit - 1;
+      if (s_last)  // everyone has arrived: ready for the next launch
+        __hip_atomic_store(p.ws_cnt + tile_id, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!s_last) return;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+    for (int s2 = 0; s2 < p.nsplit; ++s2) {
+      const float* theirs = parts + (int64_t)s2 * (kBwdWaves * WAVE_F);
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          acc[db][v] += __hip_atomic_load(theirs + (db * 16 + v) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+
   // ---- dV (P waves) and dK = -scale * (accumulated E^T Q) (E waves) of the wave's 32 keys:
-  // a lane owns one column per block and 16 key rows
+  // a lane owns one column per block and 16 key rows.  This workgroup is the only one that
+  // writes these rows in this launch, so accumulation is a plain read-modify-write.
   float* base = (p_wave ? p.dv : p.dk) + (((int64_t)b * p.Hkv + hk) * p.kv_len + kseg.start) * D + l32;
   const float f = p_wave ? 1.f : -p.scale;
 #pragma unroll
@@ -372,8 +422,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
       const int koff = koff0 + 32 * kg + acc_row(v, hh);
       if (koff < kseg.len) {
         const int64_t o = (int64_t)koff * D + db * 32;
-        if (p.add_dkv) unsafeAtomicAdd(base + o, acc[db][v] * f);
-        else base[o] = acc[db][v] * f;
+        base[o] = p.accumulate ? base[o] + acc[db][v] * f : acc[db][v] * f;
       }
     }
 }
@@ -413,12 +462,17 @@ int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
   if (busy > 0 && busy < 256) nsplit = (int)std::min<int64_t>((256 + busy - 1) / busy, 16);
   if (diag && busy * nsplit <= 512) nsplit *= 2;
   nsplit = (int)std::min<int64_t>(nsplit, q_tiles);
+  if (busy > kWsCounters) nsplit = 1;  // (cannot happen: loops are only shared when key tiles are few)
   p.nsplit = nsplit;
-  p.add_dkv = (accumulate || nsplit > 1) ? 1 : 0;
+  p.accumulate = accumulate ? 1 : 0;
   const int64_t total = base * nsplit;
   if (total > 0x3ffffff0) return fail(LOONG_E_UNSUPPORTED, "backward grid too large");
   p.map = make_work_map((int64_t)p.Hkv * p.B, (int64_t)p.kt_total * nsplit);
-  if ((nsplit > 1 || unseen_keys) && !accumulate) {
+  if (nsplit > 1) {
+    const size_t bytes = (size_t)total * kBwdWaves * (D / 32) * 16 * 64 * sizeof(float);
+    if (int rc = workspace_get(bytes, &p.ws_cnt, &p.ws_part)) return rc;
+  }
+  if (unseen_keys && !accumulate) {
     const int64_t n4 = (int64_t)p.B * p.Hkv * p.kv_len * D / 4;
     zero_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st>>>(n4, reinterpret_cast<float4*>(p.dk),
                                                                           reinterpret_cast<float4*>(p.dv));

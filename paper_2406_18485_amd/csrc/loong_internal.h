@@ -1,5 +1,6 @@
 // Internal declarations shared by the host side of the library (not part of the ABI).
 #pragma once
+#include <stddef.h>
 #include <stdint.h>
 #include "loong.h"
 
@@ -32,6 +33,12 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // Map a hipError_t (as int) of the last launch to the ABI status.
 int check_launch(const char* what);
+
+// The library's per-device block for partial results (workspace.hip): kWsCounters counters,
+// all zero between launches, and at least `payload_bytes` of payload.  May allocate (and
+// then synchronises the device); not under stream capture.
+constexpr int kWsCounters = 16384;
+int workspace_get(size_t payload_bytes, uint32_t** counters, float** payload);
 
 }  // namespace loong
 
