@@ -32,7 +32,7 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script (summaries under profiles/), scaled by the same counters' reading for a copy kernel
 # of known size; null for workloads that were not profiled.
-TRAFFIC: dict = {"mha7b_32k": 64.4e6}  # 25.4 MiB read + 36.0 MiB written per bwd_dkv launch
+TRAFFIC: dict = {"mha7b_32k": 77.7e6}  # 34.1 MiB read + 40.0 MiB written per bwd_dkv launch (average of the eight steps)
 
 
 def pairs_per_head(cfg) -> int:
