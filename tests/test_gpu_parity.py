@@ -231,6 +231,28 @@ def test_backward_is_bit_reproducible(idx, c):
             assert torch.equal(got, want)
 
 
+def test_partial_sums_of_one_launch_never_reach_the_next():
+    """Workgroups that share a query loop exchange partial dK/dV through one buffer that every launch reuses.
+    Two problems of the same shape and different data, run alternately, must each reproduce their own first
+    results bit for bit (and those match the oracle): a partial sum left over from the other problem, read
+    in place of a fresh one, would show."""
+    base = CONFIGS[1].shrunk(448)
+    runs = []
+    for seed in (11, 12):
+        cfg = RingConfig(**{**base.__dict__, "seed": seed, "name": f"{base.name}/seed{seed}"})
+        inp = make_inputs(cfg)
+        runs.append((Replayed(cfg, inp), oracle_full(cfg, inp)))
+    firsts = []
+    for run, ref in runs:
+        check_full(run.run(), ref)
+        firsts.append([t.clone() for t in (run.rep.dq, run.rep.dk, run.rep.dv)])
+    for _ in range(3):
+        for (run, _), first in zip(runs, firsts):
+            run.run()
+            for got, want in zip((run.rep.dq, run.rep.dk, run.rep.dv), first):
+                assert torch.equal(got, want)
+
+
 @pytest.mark.parametrize("idx,c", [(3, 192), (1, 128), (2, 160)])
 def test_two_buffer_forward_equals_the_resident_replay(idx, c):
     """The receive-buffer schedule of Alg. 2 (inner and outer ring buffers, copies on side streams) must give
