@@ -161,6 +161,10 @@ LOONG_API int loong_init_running(int64_t rows, int32_t head_dim, float* out, flo
 LOONG_API int loong_finalize_out(int64_t rows, int32_t head_dim, const float* out, void* o, int32_t dtype,
                        void* stream);
 
+/* Bytes of partial results loong_attn_step_bwd would park in the library's block for this
+ * step (0 when no query loop is shared); host-only. */
+LOONG_API int loong_workspace_bytes(const loong_step_desc* desc, int64_t* bytes);
+
 /* Make the library's block for partial results on the current device at least `bytes`
  * large now (host-synchronous; see loong_attn_step_bwd). */
 LOONG_API int loong_reserve_workspace(int64_t bytes);

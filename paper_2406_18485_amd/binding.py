@@ -21,7 +21,7 @@ EXPORTS = (
     "loong_zigzag_mask", "loong_attn_step_fwd", "loong_lse_merge", "loong_attn_step_bwd",
     "loong_bwd_delta", "loong_init_running", "loong_finalize_out", "loong_validate_step",
     "loong_last_error", "loong_version", "loong_mfma_probe", "loong_cost_model", "loong_cost_search",
-    "loong_permute_rows", "loong_reduce_replicas", "loong_reserve_workspace",
+    "loong_permute_rows", "loong_reduce_replicas", "loong_reserve_workspace", "loong_workspace_bytes",
 )
 
 
@@ -75,6 +75,7 @@ lib.loong_finalize_out.argtypes = [_i64, _i32, _vp, _vp, _i32, _vp]
 lib.loong_validate_step.argtypes = [C.POINTER(StepDesc)]
 lib.loong_mfma_probe.argtypes = [_i32, _i32, _vp, _vp]
 lib.loong_reserve_workspace.argtypes = [_i64]
+lib.loong_workspace_bytes.argtypes = [C.POINTER(StepDesc), C.POINTER(C.c_int64)]
 lib.loong_permute_rows.argtypes = [C.POINTER(_i64), C.POINTER(_i64), C.POINTER(_i64), _i64, _vp, _vp, _vp]
 lib.loong_reduce_replicas.argtypes = [_i64, _i32, _i64, _vp, _vp, _vp]
 lib.loong_cost_model.argtypes = [C.POINTER(CostIn), C.POINTER(CostOut)]
@@ -149,6 +150,13 @@ def permute_rows(n, in_stride, out_stride, row_bytes: int, src, dst, stream=None
 
 def reduce_replicas(heads: int, rep: int, elems_per_head: int, src, dst, stream=None):
     _check(lib.loong_reduce_replicas(heads, rep, elems_per_head, _ptr(src), _ptr(dst), _stream(stream)))
+
+
+def workspace_bytes(desc) -> int:
+    """Bytes of partial results the backward step of this descriptor parks in the library's block."""
+    n = C.c_int64(0)
+    _check(lib.loong_workspace_bytes(C.byref(desc), C.byref(n)))
+    return n.value
 
 
 def reserve_workspace(nbytes: int):

@@ -44,4 +44,13 @@ int loong_attn_step_bwd(const loong_step_desc* desc, const void* q, const void* 
              : launch_bwd_bf16(*desc, g, q, k, v, d_o, lse, delta, dq, dk, dv, stream);
 }
 
+int loong_workspace_bytes(const loong_step_desc* desc, int64_t* bytes) {
+  clear_error();
+  StepGeom g;
+  if (int rc = check_step(desc, &g)) return rc;
+  if (!bytes) return fail(LOONG_E_NULL, "loong_workspace_bytes: NULL result");
+  *bytes = desc->dtype == LOONG_FP32 ? 0 : bwd_workspace_bytes_bf16(*desc, g);
+  return LOONG_OK;
+}
+
 }  // extern "C"

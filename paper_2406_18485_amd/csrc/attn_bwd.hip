@@ -435,43 +435,63 @@ __global__ __launch_bounds__(256) void zero_kernel(int64_t n4, float4* a, float4
   }
 }
 
-template <class E, int D>
-int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
+// Work list of a step: key tiles per key segment (only segments some query can see), whether
+// a key segment nobody sees exists (its gradients are cleared by the zero pass), and how many
+// workgroups share the query loop of a key tile: more than one when the listed tiles are
+// fewer than the CUs, and twice as many when a diagonal block makes the loop lengths uneven.
+struct SplitPlan {
+  int nkt[2], kt_total, nsplit;
+  bool unseen_keys;
+  int64_t busy;  // listed key tiles x kv heads x batch
+};
+
+SplitPlan plan_split(const StepGeom& g, int G, int Hkv, int B, int q_len) {
   constexpr int BM = kBwdBM, BN = kBwdBN;
-  // Only key tiles that some query can see are listed (eight equal ranges of the list, one
-  // per XCD, then carry equal work); key segments nobody sees are cleared by the zero pass.
-  // The query-tile loop is spread over several workgroups when the listed tiles are fewer
-  // than the CUs, and once more when a diagonal block makes their loop lengths uneven.
-  p.kt_total = 0;
-  bool diag = false, unseen_keys = false;
+  SplitPlan s{};
+  bool diag = false;
   for (int kb = 0; kb < 2; ++kb) {
     bool seen = false;
-    if (kb < p.g.nk)
-      for (int a = 0; a < p.g.nq; ++a) {
-        seen |= p.g.cls[a][kb] != LOONG_SKIP && p.g.q[a].len > 0;
-        diag |= p.g.cls[a][kb] == LOONG_DIAG;
+    if (kb < g.nk)
+      for (int a = 0; a < g.nq; ++a) {
+        seen |= g.cls[a][kb] != LOONG_SKIP && g.q[a].len > 0;
+        diag |= g.cls[a][kb] == LOONG_DIAG;
       }
-    p.nkt[kb] = seen ? (p.g.k[kb].len + BN - 1) / BN : 0;
-    p.kt_total += p.nkt[kb];
-    unseen_keys |= kb < p.g.nk && !seen && p.g.k[kb].len > 0;
+    s.nkt[kb] = seen ? (g.k[kb].len + BN - 1) / BN : 0;
+    s.kt_total += s.nkt[kb];
+    s.unseen_keys |= kb < g.nk && !seen && g.k[kb].len > 0;
   }
-  const int64_t base = (int64_t)p.kt_total * p.Hkv * p.B;
-  const int64_t busy = base;
+  s.busy = (int64_t)s.kt_total * Hkv * B;
   int nsplit = 1;
-  const int64_t q_tiles = std::max<int64_t>((int64_t)p.G * ((p.q_len + BM - 1) / BM), 1);
-  if (busy > 0 && busy < 256) nsplit = (int)std::min<int64_t>((256 + busy - 1) / busy, 16);
-  if (diag && busy * nsplit <= 512) nsplit *= 2;
+  const int64_t q_tiles = std::max<int64_t>((int64_t)G * ((q_len + BM - 1) / BM), 1);
+  if (s.busy > 0 && s.busy < 256) nsplit = (int)std::min<int64_t>((256 + s.busy - 1) / s.busy, 16);
+  if (diag && s.busy * nsplit <= 512) nsplit *= 2;
   nsplit = (int)std::min<int64_t>(nsplit, q_tiles);
-  if (busy > kWsCounters) nsplit = 1;  // (cannot happen: loops are only shared when key tiles are few)
+  if (s.busy > kWsCounters) nsplit = 1;  // (cannot happen: loops are only shared when key tiles are few)
+  s.nsplit = nsplit;
+  return s;
+}
+
+// bytes of partial sums one launch parks in the workspace
+size_t partial_bytes(const SplitPlan& s, int head_dim) {
+  return s.nsplit > 1 ? (size_t)s.busy * s.nsplit * kBwdWaves * (head_dim / 32) * 16 * 64 * sizeof(float) : 0;
+}
+
+template <class E, int D>
+int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
+  // Only key tiles that some query can see are listed (eight equal ranges of the list, one
+  // per XCD, then carry equal work).
+  const SplitPlan plan = plan_split(p.g, p.G, p.Hkv, p.B, p.q_len);
+  p.nkt[0] = plan.nkt[0]; p.nkt[1] = plan.nkt[1]; p.kt_total = plan.kt_total;
+  const bool unseen_keys = plan.unseen_keys;
+  const int64_t base = plan.busy;
+  const int nsplit = plan.nsplit;
   p.nsplit = nsplit;
   p.accumulate = accumulate ? 1 : 0;
   const int64_t total = base * nsplit;
   if (total > 0x3ffffff0) return fail(LOONG_E_UNSUPPORTED, "backward grid too large");
   p.map = make_work_map((int64_t)p.Hkv * p.B, (int64_t)p.kt_total * nsplit);
-  if (nsplit > 1) {
-    const size_t bytes = (size_t)total * kBwdWaves * (D / 32) * 16 * 64 * sizeof(float);
-    if (int rc = workspace_get(bytes, &p.ws_cnt, &p.ws_part)) return rc;
-  }
+  if (nsplit > 1)
+    if (int rc = workspace_get(partial_bytes(plan, D), &p.ws_cnt, &p.ws_part)) return rc;
   if (unseen_keys && !accumulate) {
     const int64_t n4 = (int64_t)p.B * p.Hkv * p.kv_len * D / 4;
     zero_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st>>>(n4, reinterpret_cast<float4*>(p.dk),
@@ -506,6 +526,11 @@ int launch_bwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
   }
   if (d.flags & LOONG_BWD_ONLY_DKV) return LOONG_OK;
   return launch_bwd_dq_bf16(d, g, q, k, v, d_o, lse, delta, dq, stream);
+}
+
+int64_t bwd_workspace_bytes_bf16(const loong_step_desc& d, const StepGeom& g) {
+  if (d.kv_len == 0 || d.batch == 0 || (d.flags & LOONG_BWD_ONLY_DQ)) return 0;
+  return (int64_t)partial_bytes(plan_split(g, d.n_q_heads / d.n_kv_heads, d.n_kv_heads, d.batch, d.q_len), d.head_dim);
 }
 
 }  // namespace loong

@@ -55,6 +55,7 @@ int launch_fwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
 int launch_bwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, const void* k,
                     const void* v, const void* d_o, const float* lse, const float* delta, float* dq,
                     float* dk, float* dv, void* stream);
+int64_t bwd_workspace_bytes_bf16(const loong_step_desc& d, const StepGeom& g);
 int launch_bwd_dq_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, const void* k,
                        const void* v, const void* d_o, const float* lse, const float* delta, float* dq,
                        void* stream);

@@ -148,6 +148,24 @@ def test_layout_and_probe_entry_points_validate_before_touching_a_device():
     assert lib.loong_mfma_probe(1, 1, None, None) == P.E_NULL
 
 
+def test_workspace_bytes_follows_the_split_of_the_query_loops():
+    """Few key tiles (fewer than CUs): the query loops are shared and partial sums are parked; many: nothing is."""
+    per_item = 8 * (128 // 32) * 16 * 64 * 4            # one (key tile, split) slot: eight waves' accumulators
+    small = _good(n_q_heads=8, n_kv_heads=8, q_len=4096, kv_len=4096, chunk_len=2048, causal=1,
+                  q_chunk=(7, 8), kv_chunk=(3, 12))      # both local chunks see the early key chunk only: 16 tiles x 8 heads
+    assert P.workspace_bytes(small) == 128 * 2 * per_item
+    big = _good(n_q_heads=8, n_kv_heads=8, q_len=16384, kv_len=16384, chunk_len=8192, causal=1,
+                q_chunk=(0, 31), kv_chunk=(5, 26))
+    assert P.workspace_bytes(big) == 0
+    big.flags = P.BWD_ONLY_DQ
+    small.flags = P.BWD_ONLY_DQ
+    assert P.workspace_bytes(small) == 0
+    assert P.workspace_bytes(_good(dtype=P.FP32, head_dim=64, n_q_heads=2, n_kv_heads=2, q_len=256, kv_len=256, chunk_len=128)) == 0
+    lib = P.binding.lib
+    import ctypes as C
+    assert lib.loong_workspace_bytes(C.byref(small), None) == P.E_NULL
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
