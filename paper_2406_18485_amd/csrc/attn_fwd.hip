@@ -265,6 +265,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
   }
 
   wait_vmcnt<0>();
+  const bool stage_late = PD == 1 && wave >= kFwdWaves / 2;  // waves w and w + 4 share a SIMD
 
   for (int t = 0; t < total_t; ++t) {
     // this wave's loads of tile t have landed when at most the later tiles' are outstanding
@@ -273,11 +274,21 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
     else if (later == 1) wait_vmcnt<2 * KI>();
     else wait_vmcnt<0>();
     __syncthreads();  // every wave's part of tile t is in LDS; everyone has finished tile t-1
-    if (t + PD < total_t) issue_tile(t + PD);  // into the buffer tile t-1 used
+    // Tile t+PD goes into the buffer tile t-1 used.  A wave is held at each staging load
+    // until the address unit has taken it (16 clocks per load, one unit per CU).  With a
+    // single tile of look-ahead (the 64 KB tiles of four key splits) that hold is the largest
+    // part of an iteration, and the two waves of a SIMD then stage at different times: one
+    // right here, its partner behind its score product, each while the other computes
+    // (3-5 % there; with deeper look-ahead staggering measured 7-10 % slower).
+    const bool more = t + PD < total_t;
+    if (more && !stage_late) issue_tile(t + PD);
 
     int j0, klen;
     bool isdiag;
-    if (!my_keys(t, j0, klen, isdiag)) continue;
+    if (!my_keys(t, j0, klen, isdiag)) {
+      if (more && stage_late) issue_tile(t + PD);
+      continue;
+    }
     const unsigned char* Kt = smem + (t % NBUF) * C::BUF_B + ksp * BNS * ROWB;
     const unsigned char* Vt = smem + (t % NBUF) * C::BUF_B + C::TILE_B + ksp * BNS * ROWB;
 
@@ -302,6 +313,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
         s[it % NJB] = E::mfma(ring[it % (PF + 1)], qf[it / NJB], it < NJB ? zero : s[it % NJB]);
       });
     }
+    if (more && stage_late) issue_tile(t + PD);
     // ---- mask (diagonal or ragged end only)
     if (j0 + BNS > klen || (isdiag && j0 + BNS - 1 > wrow0)) {
 #pragma unroll
