@@ -32,6 +32,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 
 #include "device_utils.h"
 #include "loong_internal.h"
@@ -465,6 +466,10 @@ SplitPlan plan_split(const StepGeom& g, int G, int Hkv, int B, int q_len) {
   const int64_t q_tiles = std::max<int64_t>((int64_t)G * ((q_len + BM - 1) / BM), 1);
   if (s.busy > 0 && s.busy < 256) nsplit = (int)std::min<int64_t>((256 + s.busy - 1) / s.busy, 16);
   if (diag && s.busy * nsplit <= 512) nsplit *= 2;
+  // The last workgroup of a key tile adds up all its partial sums alone, at one CU's memory
+  // rate (about 1.1 us per split), while a split shortens the loop by q_tiles x 1.9 us / n:
+  // past n = sqrt(1.76 q_tiles) more splits lengthen the launch.
+  nsplit = (int)std::min<int64_t>(nsplit, std::max<int64_t>(2, (int64_t)std::sqrt(1.76 * (double)q_tiles)));
   nsplit = (int)std::min<int64_t>(nsplit, q_tiles);
   if (s.busy > kWsCounters) nsplit = 1;  // (cannot happen: loops are only shared when key tiles are few)
   s.nsplit = nsplit;
