@@ -99,7 +99,8 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd_kernel(const FwdParams p) 
   const int row0_wg = tile * BMH;
   const Segment qseg = qa ? p.g.q[1] : p.g.q[0];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: what derives from it stays scalar
   const int rb = wave % NRB, ksp = wave / NRB;  // row block, key split
   const int gq = rb % p.GS, rslot = rb / p.GS;
   const int h = hg * p.GS + gq, hk = h / p.G;
