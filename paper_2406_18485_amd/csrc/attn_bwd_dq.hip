@@ -124,6 +124,9 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
     dl = p.delta[r1];
   }
 
+  floatx16_t ndl;  // -delta of the lane's row in every element: where the dP chains start
+#pragma unroll
+  for (int v = 0; v < 16; ++v) ndl[v] = -dl;
   floatx16_t acc[NDB];  // dQ^T of the wave's rows (without the softmax scale)
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
@@ -242,18 +245,19 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
         floatx16_t zero;
 #pragma unroll
         for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+        // (the dP chain starts from -delta of the lane's row, so it ends as dP - delta)
         static_for<0, NIT>([&](auto i) {
           constexpr int it = i.value, ks = it >> 1;
           if constexpr (it + PF < NIT) ring[(it + PF) % (PF + 1)] = row_frag(it + PF);
           __builtin_amdgcn_sched_barrier(0);
-          if constexpr (it & 1) dp = E::mfma(ring[it % (PF + 1)], dof[ks], ks ? dp : zero);
+          if constexpr (it & 1) dp = E::mfma(ring[it % (PF + 1)], dof[ks], ks ? dp : ndl);
           else s = E::mfma(ring[it % (PF + 1)], qf[ks], ks ? s : zero);
         });
       }
       // ---- dS^T = P^T (dP^T - delta), the softmax scale is applied to the sums at the end
       float e[16];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) e[v] = fast_exp2(fmaf(s[v], p.c, nl)) * (dp[v] - dl);
+      for (int v = 0; v < 16; ++v) e[v] = fast_exp2(fmaf(s[v], p.c, nl)) * dp[v];
       if (j0 + 32 > klen || (isdiag && j0 + 31 > wrow0)) {  // diagonal or ragged end only
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
