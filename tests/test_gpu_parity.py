@@ -369,6 +369,13 @@ def test_non_causal_ragged_lengths(dtype, nq, nk):
     _direct(dtype, 2, 4, 2, 128 if dtype == "bf16" else 32, nq, nk, seed=nq + nk)
 
 
+@pytest.mark.parametrize("hq,hkv,d,nq,nk", [(2, 2, 128, 1900, 200), (4, 1, 64, 1000, 130), (8, 8, 128, 700, 100)])
+def test_few_key_tiles_many_query_tiles(hq, hkv, d, nq, nk):
+    """Far fewer key tiles than CUs: several workgroups share a key tile's query loop, their number
+    capped by the cost of the final summation (7, 10 and 4 here: uneven shares of the loop)."""
+    _direct("bf16", 1, hq, hkv, d, nq, nk, seed=nq * 7 + nk)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 def test_token_major_strides_and_accumulating_dkv(dtype):
     _direct(dtype, 2, 4, 2, 64, 130, 190, seed=3, strided=True, accum=True)
