@@ -12,9 +12,23 @@ LLAMA7B = dict(S=131072, D=4096, H=32)
 
 
 # ------------------------------------------------------------------ pins of the oracle
+def _golden():
+    """tests/golden/paper_worked_values.txt: name | value | unit | citation."""
+    import os
+    out = {}
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_worked_values.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, value, unit, _cite = [x.strip() for x in line.split("|", 3)]
+                out[name] = (float(value), unit)
+    return out
+
+
 def test_worked_size_from_the_paper():
     # Sec. "Inefficient Performance" (motivation): GQA, 128K tokens, 8 GPUs in one ring -> 64 MB per step
-    assert cm.size_kv(131072, 4096, 32, 8, d_hp=1, d_cp=8) == 64 * MIB
+    value, unit = _golden()["kv_bytes_per_ring_step_gqa_128k_8gpus"]
+    assert unit == "MiB"
+    assert cm.size_kv(131072, 4096, 32, 8, d_hp=1, d_cp=8) == value * MIB
 
 
 def test_size_kv_depends_on_d_sp_only_without_replication():
