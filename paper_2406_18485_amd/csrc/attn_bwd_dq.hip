@@ -283,8 +283,17 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
     }
   }
 
-  // ---- sum the key splits: splits 1.. park their dQ^T in LDS, split 0 adds them in order
+  // ---- sum the key splits: splits 1.. park their dQ^T in LDS, split 0 adds them in order.
+  // Split 0 requests its rows of dQ first: the round trip to memory runs while the others park.
+  float* const dq_row = p.dq + b * p.os[0] + h * p.os[1] + (int64_t)my_row * p.os[2];
+  float4 old[NDB][4];
   if (KS > 1) {
+    if (ksp == 0 && row_ok) {
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) old[db][vq] = *reinterpret_cast<const float4*>(dq_row + db * 32 + 8 * vq + 4 * hh);
+    }
     __syncthreads();  // all reads of the last tile are done: the tile buffers are reused
     float4* slots = reinterpret_cast<float4*>(smem);
     if (ksp > 0) {
@@ -313,13 +322,12 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
 
   // ---- dQ row += scale * sum: register 4 vq + r of block db is column 32 db + 8 vq + 4 hh + r
   if (row_ok) {
-    float* dq_row = p.dq + b * p.os[0] + h * p.os[1] + (int64_t)my_row * p.os[2];
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
         float4* dst = reinterpret_cast<float4*>(dq_row + db * 32 + 8 * vq + 4 * hh);
-        float4 x = *dst;
+        float4 x = KS > 1 ? old[db][vq] : *dst;
         x.x = fmaf(acc[db][4 * vq + 0], p.scale, x.x); x.y = fmaf(acc[db][4 * vq + 1], p.scale, x.y);
         x.z = fmaf(acc[db][4 * vq + 2], p.scale, x.z); x.w = fmaf(acc[db][4 * vq + 3], p.scale, x.w);
         *dst = x;
