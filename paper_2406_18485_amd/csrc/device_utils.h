@@ -84,6 +84,14 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// The value of the lane one (two) places away inside each group of four lanes.
+__device__ __forceinline__ float quad_swap1(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, false));  // quad_perm [1,0,3,2]
+}
+__device__ __forceinline__ float quad_swap2(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xf, 0xf, false));  // quad_perm [2,3,0,1]
+}
+
 // ---- global memory -> LDS without registers -------------------------------------------------
 // 16 (or 4) bytes per lane from global memory straight into LDS: lane l's data lands at
 // lds_addr + 16 l (4 l), lds_addr uniform over the wave.  Written as assembly so that the
