@@ -71,8 +71,8 @@ def cpu_baseline(cfg, inp, budget_rows: int):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=48)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=None, help="timed passes (default: 200 for the 32K shape, fewer for the long ones)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed passes before them (default: as many as --steps' default: the clock needs ~0.3 s of load to settle)")
     ap.add_argument("--config", type=int, default=1, help="index into workloads.CONFIGS (1 = 7B MHA shard, 32K)")
     ap.add_argument("--cpu-rows", type=int, default=-1,
                     help="rows of the oracle sample (0: skip the CPU baseline; -1: sized for about 15 s of host work)")
@@ -96,6 +96,13 @@ def main():
     from workloads import CONFIGS, make_inputs
 
     cfg = CONFIGS[args.config]
+    # default pass counts: about 0.3 s of load before the timed region (the clock climbs from idle
+    # for that long; 10 warm-up passes of the 32K shape read 1 % low), about as much inside it
+    passes = {0: 200, 1: 200, 2: 32, 3: 10, 4: 4}.get(args.config, 10)
+    if args.steps is None:
+        args.steps = passes
+    if args.warmup is None:
+        args.warmup = passes
     if args.rank is not None:
         if not 0 <= args.rank < cfg.cp:
             sys.exit(f"--rank must be in [0, {cfg.cp})")
