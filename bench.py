@@ -139,7 +139,8 @@ def main():
         d.flags = flags
         P.attn_step_bwd(d, run.q, run.k_by_src[src], run.v_by_src[src], None, run.d_o, rep.lse, rep.delta,
                         None if flags & P.BWD_ONLY_DKV else rep.dq,
-                        None if flags & P.BWD_ONLY_DQ else rep.dk[src], None if flags & P.BWD_ONLY_DQ else rep.dv[src])
+                        None if flags & P.BWD_ONLY_DQ else rep.dk[src], None if flags & P.BWD_ONLY_DQ else rep.dv[src],
+                        rep.workspace)
 
     def one_pass(sampled=(), every=None):
         """One pass of the path.  `sampled`: {step: (ev0, ev1)} brackets the dK/dV kernel of those

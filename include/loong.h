@@ -15,8 +15,12 @@
  *   - every tensor pointer is a DEVICE pointer owned by the caller and must stay valid
  *     until the work enqueued on `stream` has finished; descriptors and the small
  *     arrays of loong_zigzag_mask are HOST memory read during the call.
- *   - nothing allocates, frees or synchronises; kernels are enqueued on `stream`
- *     (a hipStream_t passed as void*, NULL = the default stream).
+ *   - nothing allocates, frees or synchronises, and the library keeps no state between
+ *     calls (apart from the error text and a write-once table of device properties);
+ *     kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream); scratch memory a call needs is handed in by the caller (`workspace`).
+ *   - the kernels are built for gfx950 only: on any other device the step calls return
+ *     LOONG_E_UNSUPPORTED; launch shapes follow the device's compute-unit count.
  *   - arguments are validated before anything is launched; on error nothing is enqueued.
  *   - layouts: 16-bit/fp32 inputs q,k,v,o,d_o are [batch, head, token, head_dim] with
  *     element strides given in the descriptor (head_dim stride 1).  fp32 results `out`
@@ -48,7 +52,9 @@ extern "C" {
 
 /* storage type of q, k, v, o, d_o */
 #define LOONG_BF16 0              /* bf16 MFMA kernels, head_dim 64 or 128 */
-#define LOONG_FP32 1              /* plain fp32 kernels (small cases), head_dim <= 128, multiple of 4 */
+#define LOONG_FP32 1              /* fp32 storage, head_dim <= 128, multiple of 4: a correctness path for small
+                                     cases (one wave per row, plain fp32 multiply-adds, no matrix cores, no
+                                     tiling): far from any roofline and not meant for long sequences */
 #define LOONG_FP16 2              /* the MFMA kernels on IEEE half storage (the 16-bit type Sec. "Performance
                                      Analysis" sizes the tensors in), head_dim 64 or 128 */
 
@@ -63,6 +69,11 @@ extern "C" {
 #define LOONG_COMPUTE_DELTA  4    /* bwd: fill `delta` from o and d_o before the step */
 #define LOONG_BWD_ONLY_DKV   8    /* bwd: compute dk/dv only (dq may be NULL and is not touched) */
 #define LOONG_BWD_ONLY_DQ    16   /* bwd: compute this step's share of dq only (dk, dv may be NULL) */
+/* Tuning/testing knob of the 16-bit kernels that own query rows (forward, dQ): bits 8..10 of
+ * `flags` hold 1, 2 or 4 to force that many key splits per workgroup (waves that share the
+ * same rows and divide every staged key tile); 0 = chosen from the shape and the device. */
+#define LOONG_KEY_SPLITS_SHIFT 8
+#define LOONG_KEY_SPLITS(n)  ((n) << LOONG_KEY_SPLITS_SHIFT)
 
 typedef struct loong_step_desc {
   int32_t batch;
@@ -135,18 +146,20 @@ LOONG_API int loong_lse_merge(int64_t rows, int32_t head_dim, float* out, float*
  * with LOONG_ACCUM_DKV (a plain read-modify-write: two calls that add into the same dk, dv
  * must be ordered).  dk, dv are bit-reproducible too: when a step has too few key tiles to
  * fill the chip, several workgroups share a key tile's query loop and the last one to
- * arrive adds their partial sums in a fixed order.  Those partial sums live in a block of
- * device memory the library owns (one per device, allocated on first use, grown on demand,
- * up to about 64 MiB): calls that use it on one device must be ordered on one stream, and
- * a call that has to allocate or grow it synchronises the device and fails under stream
- * capture (LOONG_E_HIP) - run the step once eagerly, or call loong_reserve_workspace,
- * before capturing.  The bf16/fp16 kernels only; the fp32 kernels need no such block.
+ * arrive adds their partial sums in a fixed order.  Those partial sums and their arrival
+ * counters live in `workspace`, device memory of the caller's, 16-byte aligned, at least
+ * loong_workspace_bytes(desc) bytes (that may be 0: then `workspace` may be NULL).  It
+ * may hold anything on entry (the call clears what it counts in with a kernel of its own on
+ * `stream`) and holds nothing of value afterwards; calls that share one workspace must be
+ * ordered on one stream.  A missing or too small workspace is LOONG_E_NULL / LOONG_E_SHAPE
+ * and nothing is enqueued.  The bf16/fp16 kernels only; the fp32 kernels need none.
  * The two halves run as two kernels on `stream`; LOONG_BWD_ONLY_DKV / LOONG_BWD_ONLY_DQ
  * run one of them (both flags together: LOONG_E_UNSUPPORTED).
  */
 LOONG_API int loong_attn_step_bwd(const loong_step_desc* desc, const void* q, const void* k, const void* v,
                         const void* o, const void* d_o, const float* lse, float* delta,
-                        float* dq, float* dk, float* dv, void* stream);
+                        float* dq, float* dk, float* dv, void* workspace, int64_t workspace_bytes,
+                        void* stream);
 
 /* delta_i = sum_k d_o_ik * o_ik for every row; o, d_o in desc->dtype with q_stride. */
 LOONG_API int loong_bwd_delta(const loong_step_desc* desc, const void* o, const void* d_o, float* delta,
@@ -161,13 +174,11 @@ LOONG_API int loong_init_running(int64_t rows, int32_t head_dim, float* out, flo
 LOONG_API int loong_finalize_out(int64_t rows, int32_t head_dim, const float* out, void* o, int32_t dtype,
                        void* stream);
 
-/* Bytes of partial results loong_attn_step_bwd would park in the library's block for this
- * step (0 when no query loop is shared); host-only. */
+/* Bytes of workspace loong_attn_step_bwd needs for this step (0 when no query loop is shared).
+ * Host-only; the answer depends on the compute-unit count of the current device (an MI355X's
+ * 256 when there is none to ask), so ask on the device that will run the step.  An upper bound
+ * over the steps of a replay is the maximum over its descriptors. */
 LOONG_API int loong_workspace_bytes(const loong_step_desc* desc, int64_t* bytes);
-
-/* Make the library's block for partial results on the current device at least `bytes`
- * large now (host-synchronous; see loong_attn_step_bwd). */
-LOONG_API int loong_reserve_workspace(int64_t bytes);
 
 /* Validate a descriptor exactly as the step calls do, without touching a device. */
 LOONG_API int loong_validate_step(const loong_step_desc* desc);

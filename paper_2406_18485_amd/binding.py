@@ -16,12 +16,19 @@ OK, E_NULL, E_SHAPE, E_UNSUPPORTED, E_ALIGN, E_DTYPE, E_HIP = 0, -1, -2, -3, -4,
 BF16, FP32, FP16 = 0, 1, 2
 SKIP, FULL, DIAG = 0, 1, 2
 FUSE_MERGE, ACCUM_DKV, COMPUTE_DELTA, BWD_ONLY_DKV, BWD_ONLY_DQ = 1, 2, 4, 8, 16
+KEY_SPLITS_SHIFT = 8
+
+
+def key_splits(n: int) -> int:
+    """LOONG_KEY_SPLITS(n): flag bits that force n (1, 2 or 4) key splits in the forward and dQ kernels."""
+    return n << KEY_SPLITS_SHIFT
+
 
 EXPORTS = (
     "loong_zigzag_mask", "loong_attn_step_fwd", "loong_lse_merge", "loong_attn_step_bwd",
     "loong_bwd_delta", "loong_init_running", "loong_finalize_out", "loong_validate_step",
     "loong_last_error", "loong_version", "loong_mfma_probe", "loong_cost_model", "loong_cost_search",
-    "loong_permute_rows", "loong_reduce_replicas", "loong_reserve_workspace", "loong_workspace_bytes",
+    "loong_permute_rows", "loong_reduce_replicas", "loong_workspace_bytes",
 )
 
 
@@ -68,13 +75,12 @@ lib.loong_zigzag_mask.argtypes = [_i32, _i32, _i32, _i32, C.POINTER(_i32), C.POI
                                   C.POINTER(C.c_uint8)]
 lib.loong_attn_step_fwd.argtypes = [C.POINTER(StepDesc), _vp, _vp, _vp, _vp, _vp, _vp]
 lib.loong_lse_merge.argtypes = [_i64, _i32, _vp, _vp, _vp, _vp, _vp]
-lib.loong_attn_step_bwd.argtypes = [C.POINTER(StepDesc)] + [_vp] * 11
+lib.loong_attn_step_bwd.argtypes = [C.POINTER(StepDesc)] + [_vp] * 11 + [_i64, _vp]
 lib.loong_bwd_delta.argtypes = [C.POINTER(StepDesc), _vp, _vp, _vp, _vp]
 lib.loong_init_running.argtypes = [_i64, _i32, _vp, _vp, _vp]
 lib.loong_finalize_out.argtypes = [_i64, _i32, _vp, _vp, _i32, _vp]
 lib.loong_validate_step.argtypes = [C.POINTER(StepDesc)]
 lib.loong_mfma_probe.argtypes = [_i32, _i32, _vp, _vp]
-lib.loong_reserve_workspace.argtypes = [_i64]
 lib.loong_workspace_bytes.argtypes = [C.POINTER(StepDesc), C.POINTER(C.c_int64)]
 lib.loong_permute_rows.argtypes = [C.POINTER(_i64), C.POINTER(_i64), C.POINTER(_i64), _i64, _vp, _vp, _vp]
 lib.loong_reduce_replicas.argtypes = [_i64, _i32, _i64, _vp, _vp, _vp]
@@ -153,15 +159,10 @@ def reduce_replicas(heads: int, rep: int, elems_per_head: int, src, dst, stream=
 
 
 def workspace_bytes(desc) -> int:
-    """Bytes of partial results the backward step of this descriptor parks in the library's block."""
+    """Bytes of caller-owned workspace the backward step of this descriptor needs (0: none)."""
     n = C.c_int64(0)
     _check(lib.loong_workspace_bytes(C.byref(desc), C.byref(n)))
     return n.value
-
-
-def reserve_workspace(nbytes: int):
-    """Allocate the library's block for partial results on the current device ahead of time."""
-    _check(lib.loong_reserve_workspace(nbytes))
 
 
 def mfma_probe(workgroups: int, iters: int, sink, stream=None):
@@ -210,9 +211,14 @@ def lse_merge(rows: int, head_dim: int, out, lse, block_out, block_lse, stream=N
                                _stream(stream)))
 
 
-def attn_step_bwd(desc: StepDesc, q, k, v, o, d_o, lse, delta, dq, dk, dv, stream=None):
+def attn_step_bwd(desc: StepDesc, q, k, v, o, d_o, lse, delta, dq, dk, dv, workspace=None, workspace_bytes=None,
+                  stream=None):
+    """`workspace`: a device tensor (its size in bytes is taken from it) or a raw pointer with `workspace_bytes`."""
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None or isinstance(workspace, int) else workspace.numel() * workspace.element_size()
     _check(lib.loong_attn_step_bwd(C.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse),
-                                   _ptr(delta), _ptr(dq), _ptr(dk), _ptr(dv), _stream(stream)))
+                                   _ptr(delta), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), workspace_bytes,
+                                   _stream(stream)))
 
 
 def bwd_delta(desc: StepDesc, o, d_o, delta, stream=None):

@@ -22,7 +22,7 @@ int loong_attn_step_fwd(const loong_step_desc* desc, const void* q, const void* 
 
 int loong_attn_step_bwd(const loong_step_desc* desc, const void* q, const void* k, const void* v,
                         const void* o, const void* d_o, const float* lse, float* delta, float* dq,
-                        float* dk, float* dv, void* stream) {
+                        float* dk, float* dv, void* workspace, int64_t workspace_bytes, void* stream) {
   clear_error();
   StepGeom g;
   if (int rc = check_step(desc, &g)) return rc;
@@ -36,12 +36,25 @@ int loong_attn_step_bwd(const loong_step_desc* desc, const void* q, const void* 
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || (!only_dkv && !aligned16(dq)) ||
       (!only_dq && (!aligned16(dk) || !aligned16(dv))) || (want_delta && !aligned16(o)))
     return fail(LOONG_E_ALIGN, "loong_attn_step_bwd: tensors must be 16-byte aligned");
+  if (workspace_bytes < 0) return fail(LOONG_E_SHAPE, "loong_attn_step_bwd: negative workspace size");
   if (desc->batch == 0) return LOONG_OK;
+  if (desc->dtype != LOONG_FP32) {  // scratch for shared query loops: checked before anything is enqueued
+    const int64_t need = bwd_workspace_bytes_bf16(*desc, g);
+    if (need > 0) {
+      if (!workspace)
+        return fail(LOONG_E_NULL, "loong_attn_step_bwd: this step needs a workspace of %lld bytes (loong_workspace_bytes)",
+                    (long long)need);
+      if (!aligned16(workspace)) return fail(LOONG_E_ALIGN, "loong_attn_step_bwd: the workspace must be 16-byte aligned");
+      if (workspace_bytes < need)
+        return fail(LOONG_E_SHAPE, "loong_attn_step_bwd: workspace of %lld bytes, this step needs %lld (loong_workspace_bytes)",
+                    (long long)workspace_bytes, (long long)need);
+    }
+  }
   if (want_delta)
     if (int rc = loong_bwd_delta(desc, o, d_o, delta, stream)) return rc;
   return desc->dtype == LOONG_FP32
              ? launch_bwd_f32(*desc, g, q, k, v, d_o, lse, delta, dq, dk, dv, stream)
-             : launch_bwd_bf16(*desc, g, q, k, v, d_o, lse, delta, dq, dk, dv, stream);
+             : launch_bwd_bf16(*desc, g, q, k, v, d_o, lse, delta, dq, dk, dv, workspace, workspace_bytes, stream);
 }
 
 int loong_workspace_bytes(const loong_step_desc* desc, int64_t* bytes) {

@@ -53,7 +53,7 @@ struct BwdParams {
   int accumulate;  // 1: the results are added to dk/dv instead of stored
   int nkt[2], kt_total;
   int nsplit;      // workgroups that share the query loop of one key tile
-  uint32_t* ws_cnt;  // nsplit > 1: arrival counter per (batch, kv head, key tile), zero between launches
+  uint32_t* ws_cnt;  // nsplit > 1: arrival counter per (batch, kv head, key tile), cleared before the launch
   float* ws_part;    // nsplit > 1: partial dK/dV of every (key tile, split), in accumulator layout
   WorkMap map;     // units = batch x kv heads, items = key tiles x splits
 };
@@ -299,13 +299,16 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
           nl[ib][4 * vq + 0] = L.x * -kLog2e; nl[ib][4 * vq + 1] = L.y * -kLog2e;
           nl[ib][4 * vq + 2] = L.z * -kLog2e; nl[ib][4 * vq + 3] = L.w * -kLog2e;
         }
-      if (need_mask) {
+      // a row whose LSE is -inf saw no key in the whole attention: its offset came out as +inf
+      // and must be -inf (P = 0).  One look at the tile's 64 staged values per wave finds the case.
+      const bool blind_row = __builtin_amdgcn_ballot_w64(lse_s[lane] == -INFINITY) != 0;
+      if (need_mask || blind_row) {
 #pragma unroll
         for (int ib = 0; ib < 2; ++ib)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int i_off = i0 + ib * 32 + acc_row(v, hh);
-            const bool ok = key_ok && i_off < qlen && (!isdiag || my_koff <= i_off);
+            const bool ok = key_ok && i_off < qlen && (!isdiag || my_koff <= i_off) && nl[ib][v] < INFINITY;
             nl[ib][v] = ok ? nl[ib][v] : -INFINITY;
           }
       }
@@ -365,7 +368,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
   }
 
   // ---- several workgroups shared this key tile's query loop: each parks its partial sums
-  // in the library's workspace, and the one that arrives last adds them up in split order,
+  // in the caller's workspace, and the one that arrives last adds them up in split order,
   // so the result does not depend on the order of arrival (no atomics on dK/dV).
   // The partials cross between XCDs, whose L2s are not coherent for ordinary accesses.  A
   // device-scope fence would do (release: write back the XCD's L2, acquire: invalidate it),
@@ -392,8 +395,6 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
     if (tid == 0) {
       const uint32_t before = __hip_atomic_fetch_add(p.ws_cnt + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       s_last = before == (uint32_t)p.nsplit - 1;
-      if (s_last)  // everyone has arrived: ready for the next launch
-        __hip_atomic_store(p.ws_cnt + tile_id, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (!s_last) return;
@@ -455,17 +456,25 @@ __global__ __launch_bounds__(256) void zero_kernel(int64_t n4, float4* a, float4
   }
 }
 
+// The arrival counters a launch with shared query loops uses start from zero: cleared on the
+// caller's stream right before it (a fill kernel, so the call can be captured in a graph).
+__global__ __launch_bounds__(256) void clear_counters_kernel(int n, uint32_t* cnt) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) cnt[i] = 0u;
+}
+
 // Work list of a step: key tiles per key segment (only segments some query can see), whether
 // a key segment nobody sees exists (its gradients are cleared by the zero pass), and how many
 // workgroups share the query loop of a key tile: more than one when the listed tiles are
-// fewer than the CUs, and twice as many when a diagonal block makes the loop lengths uneven.
+// fewer than the compute units (`cus`), and twice as many when a diagonal block makes the loop
+// lengths uneven.
 struct SplitPlan {
   int nkt[2], kt_total, nsplit;
   bool unseen_keys;
   int64_t busy;  // listed key tiles x kv heads x batch
 };
 
-SplitPlan plan_split(const StepGeom& g, int G, int Hkv, int B, int q_len) {
+SplitPlan plan_split(const StepGeom& g, int G, int Hkv, int B, int q_len, int cus) {
   constexpr int BM = kBwdBM, BN = kBwdBN;
   SplitPlan s{};
   bool diag = false;
@@ -483,8 +492,8 @@ SplitPlan plan_split(const StepGeom& g, int G, int Hkv, int B, int q_len) {
   s.busy = (int64_t)s.kt_total * Hkv * B;
   int nsplit = 1;
   const int64_t q_tiles = std::max<int64_t>((int64_t)G * ((q_len + BM - 1) / BM), 1);
-  if (s.busy > 0 && s.busy < 256) nsplit = (int)std::min<int64_t>((256 + s.busy - 1) / s.busy, 16);
-  if (diag && s.busy * nsplit <= 512) nsplit *= 2;
+  if (s.busy > 0 && s.busy < cus) nsplit = (int)std::min<int64_t>((cus + s.busy - 1) / s.busy, 16);
+  if (diag && s.busy * nsplit <= 2 * cus) nsplit *= 2;
   // The last workgroup of a key tile adds up all its partial sums alone, at one CU's memory
   // rate (about 1.1 us per split), while a split shortens the loop by q_tiles x 1.9 us / n:
   // past n = sqrt(1.76 q_tiles) more splits lengthen the launch.
@@ -501,10 +510,10 @@ size_t partial_bytes(const SplitPlan& s, int head_dim) {
 }
 
 template <class E, int D>
-int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
+int launch_d(BwdParams& p, bool accumulate, void* workspace, int64_t workspace_bytes, hipStream_t st) {
   // Only key tiles that some query can see are listed (eight equal ranges of the list, one
   // per XCD, then carry equal work).
-  const SplitPlan plan = plan_split(p.g, p.G, p.Hkv, p.B, p.q_len);
+  const SplitPlan plan = plan_split(p.g, p.G, p.Hkv, p.B, p.q_len, planning_cus());
   p.nkt[0] = plan.nkt[0]; p.nkt[1] = plan.nkt[1]; p.kt_total = plan.kt_total;
   const bool unseen_keys = plan.unseen_keys;
   const int64_t base = plan.busy;
@@ -514,8 +523,14 @@ int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
   const int64_t total = base * nsplit;
   if (total > 0x3ffffff0) return fail(LOONG_E_UNSUPPORTED, "backward grid too large");
   p.map = make_work_map((int64_t)p.Hkv * p.B, (int64_t)p.kt_total * nsplit);
-  if (nsplit > 1)
-    if (int rc = workspace_get(partial_bytes(plan, D), &p.ws_cnt, &p.ws_part)) return rc;
+  if (nsplit > 1) {  // (size and alignment were checked by the entry point, against the same plan)
+    if (!workspace || workspace_bytes < kWsHeadBytes + (int64_t)partial_bytes(plan, D))
+      return fail(LOONG_E_SHAPE, "loong_attn_step_bwd: workspace too small");
+    p.ws_cnt = static_cast<uint32_t*>(workspace);
+    p.ws_part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + kWsHeadBytes);
+  }
+  DeviceFacts dev;
+  if (int rc = device_facts(&dev)) return rc;
   if (unseen_keys && !accumulate) {
     const int64_t n4 = (int64_t)p.B * p.Hkv * p.kv_len * D / 4;
     zero_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st>>>(n4, reinterpret_cast<float4*>(p.dk),
@@ -523,6 +538,10 @@ int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
     if (int rc = check_launch("loong_attn_step_bwd (clear dk/dv)")) return rc;
   }
   if (total == 0) return LOONG_OK;
+  if (nsplit > 1) {
+    clear_counters_kernel<<<dim3((unsigned)((base + 255) / 256)), dim3(256), 0, st>>>((int)base, p.ws_cnt);
+    if (int rc = check_launch("loong_attn_step_bwd (clear counters)")) return rc;
+  }
   bwd_dkv_kernel<E, D><<<dim3(p.map.grid), dim3(kBwdWaves * 64), 0, st>>>(p);
   return check_launch("loong_attn_step_bwd (bf16, dK/dV)");
 }
@@ -531,7 +550,7 @@ int launch_d(BwdParams& p, bool accumulate, hipStream_t st) {
 
 int launch_bwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, const void* k,
                     const void* v, const void* d_o, const float* lse, const float* delta, float* dq,
-                    float* dk, float* dv, void* stream) {
+                    float* dk, float* dv, void* workspace, int64_t workspace_bytes, void* stream) {
   if (d.kv_len == 0) return LOONG_OK;
   BwdParams p{};
   p.q = (const uint16_t*)q; p.k = (const uint16_t*)k; p.v = (const uint16_t*)v; p.d_o = (const uint16_t*)d_o;
@@ -544,8 +563,10 @@ int launch_bwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
   const bool accumulate = d.flags & LOONG_ACCUM_DKV;
   if (!(d.flags & LOONG_BWD_ONLY_DQ)) {
     const int rc = d.dtype == LOONG_FP16
-                       ? (d.head_dim == 128 ? launch_d<Fp16, 128>(p, accumulate, st) : launch_d<Fp16, 64>(p, accumulate, st))
-                       : (d.head_dim == 128 ? launch_d<Bf16, 128>(p, accumulate, st) : launch_d<Bf16, 64>(p, accumulate, st));
+                       ? (d.head_dim == 128 ? launch_d<Fp16, 128>(p, accumulate, workspace, workspace_bytes, st)
+                                            : launch_d<Fp16, 64>(p, accumulate, workspace, workspace_bytes, st))
+                       : (d.head_dim == 128 ? launch_d<Bf16, 128>(p, accumulate, workspace, workspace_bytes, st)
+                                            : launch_d<Bf16, 64>(p, accumulate, workspace, workspace_bytes, st));
     if (rc != LOONG_OK) return rc;
   }
   if (d.flags & LOONG_BWD_ONLY_DKV) return LOONG_OK;
@@ -554,7 +575,8 @@ int launch_bwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
 
 int64_t bwd_workspace_bytes_bf16(const loong_step_desc& d, const StepGeom& g) {
   if (d.kv_len == 0 || d.batch == 0 || (d.flags & LOONG_BWD_ONLY_DQ)) return 0;
-  return (int64_t)partial_bytes(plan_split(g, d.n_q_heads / d.n_kv_heads, d.n_kv_heads, d.batch, d.q_len), d.head_dim);
+  const SplitPlan plan = plan_split(g, d.n_q_heads / d.n_kv_heads, d.n_kv_heads, d.batch, d.q_len, planning_cus());
+  return plan.nsplit > 1 ? kWsHeadBytes + (int64_t)partial_bytes(plan, d.head_dim) : 0;
 }
 
 }  // namespace loong

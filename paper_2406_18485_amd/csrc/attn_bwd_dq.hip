@@ -372,8 +372,9 @@ int launch_bwd_dq_bf16(const loong_step_desc& d, const StepGeom& g, const void* 
   for (int i = 0; i < 3; ++i) { p.qs[i] = d.q_stride[i]; p.ks[i] = d.kv_stride[i]; p.os[i] = d.o_stride[i]; }
   p.q_len = d.q_len; p.g = g; p.scale = d.softmax_scale; p.c = d.softmax_scale * kLog2e;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  // LOONG_DQ_KS (1, 2 or 4) overrides the number of key splits (tuning aid)
-  const int ks = pick_key_splits(g, p.G, p.Hq, p.B, "LOONG_DQ_KS");
+  DeviceFacts dev;
+  if (int rc = device_facts(&dev)) return rc;
+  const int ks = pick_key_splits(g, p.G, p.Hq, p.B, forced_key_splits(d.flags), dev.cus);
   if (d.dtype == LOONG_FP16) return pick_cfg<Fp16>(p, d.head_dim, ks, st);
   return pick_cfg<Bf16>(p, d.head_dim, ks, st);
 }

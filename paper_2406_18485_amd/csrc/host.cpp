@@ -43,6 +43,11 @@ int check_step(const loong_step_desc* d, StepGeom* g) {
     return fail(LOONG_E_UNSUPPORTED, "fp32 kernels take head_dim <= 128 and a multiple of 4, got %d",
                 d->head_dim);
   }
+  {
+    const int forced = (d->flags >> LOONG_KEY_SPLITS_SHIFT) & 7;
+    if (forced != 0 && forced != 1 && forced != 2 && forced != 4)
+      return fail(LOONG_E_UNSUPPORTED, "LOONG_KEY_SPLITS takes 1, 2 or 4 (0 = automatic), got %d", forced);
+  }
   if (!std::isfinite(d->softmax_scale) || d->softmax_scale <= 0.f)
     return fail(LOONG_E_SHAPE, "softmax_scale must be finite and positive");
   const int vec = half ? 8 : 4;  // elements per 16-byte access

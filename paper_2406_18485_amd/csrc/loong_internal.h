@@ -34,11 +34,28 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // Map a hipError_t (as int) of the last launch to the ABI status.
 int check_launch(const char* what);
 
-// The library's per-device block for partial results (workspace.hip): kWsCounters counters,
-// all zero between launches, and at least `payload_bytes` of payload.  May allocate (and
-// then synchronises the device); not under stream capture.
+// Facts of the current device, looked up once per device (device.hip).  device_facts fails with
+// LOONG_E_HIP when there is no device and LOONG_E_UNSUPPORTED when it is not a gfx950 part.
+struct DeviceFacts {
+  int cus;  // compute units
+};
+int device_facts(DeviceFacts* f);
+// Compute units to plan a launch for: the current device's, or those of an MI355X when no
+// device can be asked (host-only size queries on a machine without a GPU).
+constexpr int kDefaultCus = 256;
+int planning_cus();
+
+// Workspace of the backward step (caller-owned device memory): kWsCounters 32-bit arrival
+// counters, then the partial sums.  The step clears the counters it uses with a kernel of its
+// own before the kernel that counts, so the memory may hold anything when it is handed in.
 constexpr int kWsCounters = 16384;
-int workspace_get(size_t payload_bytes, uint32_t** counters, float** payload);
+constexpr int64_t kWsHeadBytes = (int64_t)kWsCounters * 4;
+
+// Key splits of the row-owning kernels forced through the descriptor's flags (0: automatic).
+inline int forced_key_splits(int flags) {
+  const int v = (flags >> LOONG_KEY_SPLITS_SHIFT) & 7;
+  return v == 1 || v == 2 || v == 4 ? v : 0;
+}
 
 }  // namespace loong
 
@@ -54,7 +71,7 @@ int launch_fwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, 
                     const void* v, float* out, float* lse, void* stream);
 int launch_bwd_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, const void* k,
                     const void* v, const void* d_o, const float* lse, const float* delta, float* dq,
-                    float* dk, float* dv, void* stream);
+                    float* dk, float* dv, void* workspace, int64_t workspace_bytes, void* stream);
 int64_t bwd_workspace_bytes_bf16(const loong_step_desc& d, const StepGeom& g);
 int launch_bwd_dq_bf16(const loong_step_desc& d, const StepGeom& g, const void* q, const void* k,
                        const void* v, const void* d_o, const float* lse, const float* delta, float* dq,

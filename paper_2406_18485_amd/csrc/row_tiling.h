@@ -2,8 +2,6 @@
 // (the forward step and the dQ pass of the backward step).  A workgroup has eight waves =
 // NRB row blocks of 32 rows x KS key splits; GS heads of one kv group share a workgroup.
 #pragma once
-#include <cstdlib>
-
 #include "loong_internal.h"
 
 namespace loong {
@@ -35,20 +33,18 @@ inline int64_t busy_row_tiles(const StepGeom& g, int bmh) {
 
 // Key splits: more splits give more workgroups, but each workgroup streams the whole visible
 // K/V of its head through its own LDS and keeps fewer rows per staged tile, so the smallest
-// split that puts a workgroup on (nearly) every CU is taken (measured on 32K..1M-token
-// shapes: one more split than that is always slower, one fewer leaves CUs idle).
-// The environment variable named by `env` (value 1, 2 or 4) overrides the choice (tuning aid).
-inline int pick_key_splits(const StepGeom& g, int G, int Hq, int B, const char* env) {
-  if (const char* e = std::getenv(env)) {
-    const int v = std::atoi(e);
-    if (v == 1 || v == 2 || v == 4) return v;
-  }
-  // a step with a diagonal block has tiles of very different length: two workgroups per CU,
+// split that puts a workgroup on (nearly) every compute unit is taken (measured on
+// 32K..1M-token shapes: one more split than that is always slower, one fewer leaves units idle).
+// `forced` (1, 2 or 4, from the descriptor's flags) overrides the choice; `cus` is the device's
+// number of compute units.
+inline int pick_key_splits(const StepGeom& g, int G, int Hq, int B, int forced, int cus) {
+  if (forced == 1 || forced == 2 || forced == 4) return forced;
+  // a step with a diagonal block has tiles of very different length: two workgroups per unit,
   // longest first, even them out
   bool diag = false;
   for (int a = 0; a < g.nq; ++a)
     for (int kb = 0; kb < g.nk; ++kb) diag |= g.cls[a][kb] == LOONG_DIAG;
-  const int64_t want = diag ? 448 : 224;
+  const int64_t want = (diag ? 2 : 1) * (int64_t)cus * 7 / 8;
   const int ks_opts[3] = {1, 2, 4};
   for (int i = 0; i < 3; ++i) {
     const int nrb = kRowWaves / ks_opts[i], gs = pick_gs(G, nrb);

@@ -26,6 +26,7 @@ class RingShape:
     dtype: int          # B.BF16 | B.FP32 | B.FP16
     scale: float
     batch: int = 1
+    extra_flags: int = 0   # OR-ed into every step descriptor (e.g. binding.key_splits(n))
 
     @property
     def L(self) -> int:
@@ -41,7 +42,7 @@ def _desc(shape: RingShape, step: dict, flags: int) -> B.StepDesc:
     return B.make_desc(batch=shape.batch, n_q_heads=shape.hq, n_kv_heads=shape.hkv, head_dim=shape.d,
                        q_len=shape.L, kv_len=shape.L, dtype=shape.dtype, softmax_scale=shape.scale,
                        causal=True, chunk_len=shape.c, q_chunk=step["q_chunk"], kv_chunk=step["kv_chunk"],
-                       flags=flags)
+                       flags=flags | shape.extra_flags)
 
 
 class RingReplay:
@@ -68,6 +69,9 @@ class RingReplay:
         self.dv = torch.empty(s.cp, s.batch, s.hkv, s.L, s.d, **f32)
         self.block_out = None
         self.block_lse = None
+        # caller-owned scratch of the backward steps: the largest any micro-step asks for
+        need = max(B.workspace_bytes(_desc(s, step, 0)) for step in self.plan)
+        self.workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=self.dev)
 
     # ---- forward: cp x (Attention [+ Update]) then the cast to the stored activation type
     def forward(self, q, k_by_src, v_by_src, fuse_merge=True, stream=None):
@@ -99,7 +103,7 @@ class RingReplay:
             flags = B.COMPUTE_DELTA if first else 0
             first = False
             B.attn_step_bwd(_desc(s, step, flags), q, k_by_src[src], v_by_src[src], self.o, d_o, self.lse,
-                            self.delta, self.dq, self.dk[src], self.dv[src], stream)
+                            self.delta, self.dq, self.dk[src], self.dv[src], self.workspace, stream=stream)
 
     # ---- forward with the receive buffers of Alg. 2: the chunk of the next micro-step arrives
     # in an inner-ring buffer while the current one is used, and the first chunk of the next

@@ -25,15 +25,21 @@ def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
     return t.to(DEV)
 
 
-def shape_of(cfg: RingConfig) -> RingShape:
+def workspace_for(desc) -> torch.Tensor:
+    """Caller-owned scratch for one backward step of this descriptor (never an empty allocation)."""
+    return torch.empty(max(P.workspace_bytes(desc), 16), dtype=torch.uint8, device=DEV)
+
+
+def shape_of(cfg: RingConfig, extra_flags: int = 0) -> RingShape:
     return RingShape(cp=cfg.cp, w=cfg.w, rank=cfg.rank, hq=cfg.hq, hkv=cfg.hkv, d=cfg.d, c=cfg.c,
-                     dtype={"bf16": P.BF16, "fp16": P.FP16, "fp32": P.FP32}[cfg.dtype], scale=cfg.scale)
+                     dtype={"bf16": P.BF16, "fp16": P.FP16, "fp32": P.FP32}[cfg.dtype], scale=cfg.scale,
+                     extra_flags=extra_flags)
 
 
 class Replayed:
     """Device tensors of one config and the results of a forward+backward replay."""
 
-    def __init__(self, cfg: RingConfig, inputs: dict | None = None):
+    def __init__(self, cfg: RingConfig, inputs: dict | None = None, extra_flags: int = 0):
         self.cfg = cfg
         self.inp = inputs if inputs is not None else make_inputs(cfg)
         c, cp = cfg.c, cfg.cp
@@ -46,7 +52,7 @@ class Replayed:
             vs.append(gather_chunks(self.inp["v_all"], ids, c)[None])
         self.k_by_src = to_dev(np.stack(ks), cfg.dtype)
         self.v_by_src = to_dev(np.stack(vs), cfg.dtype)
-        self.rep = RingReplay(shape_of(cfg), DEV)
+        self.rep = RingReplay(shape_of(cfg, extra_flags), DEV)
 
     def run(self, fuse_merge=True, backward=True):
         self.rep.forward(self.q, self.k_by_src, self.v_by_src, fuse_merge=fuse_merge)

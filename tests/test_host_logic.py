@@ -96,7 +96,7 @@ def test_entry_points_fail_before_any_launch_on_bad_arguments():
     import ctypes as C
     # NULL tensors
     assert lib.loong_attn_step_fwd(C.byref(d), None, None, None, None, None, None) == P.E_NULL
-    assert lib.loong_attn_step_bwd(C.byref(d), *([None] * 11)) == P.E_NULL
+    assert lib.loong_attn_step_bwd(C.byref(d), *([None] * 11), 0, None) == P.E_NULL
     assert lib.loong_bwd_delta(C.byref(d), None, None, None, None) == P.E_NULL
     assert lib.loong_lse_merge(4, 128, None, None, None, None, None) == P.E_NULL
     assert lib.loong_init_running(4, 128, None, None, None) == P.E_NULL
@@ -113,16 +113,16 @@ def test_entry_points_fail_before_any_launch_on_bad_arguments():
     assert lib.loong_lse_merge(0, 128, 0x1000, 0x1000, 0x1000, 0x1000, None) == P.OK
     assert lib.loong_attn_step_fwd(C.byref(_good(batch=0)), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, None) == P.OK
     dd = _good(flags=P.COMPUTE_DELTA)
-    assert lib.loong_attn_step_bwd(C.byref(dd), 16, 16, 16, None, 16, 16, 16, 16, 16, 16, None) == P.E_NULL
+    assert lib.loong_attn_step_bwd(C.byref(dd), 16, 16, 16, None, 16, 16, 16, 16, 16, 16, None, 0, None) == P.E_NULL
     # the one-sided backward flags: exclusive, and each lifts the NULL check of the other side's outputs only
     both = _good(flags=P.BWD_ONLY_DKV | P.BWD_ONLY_DQ)
-    assert lib.loong_attn_step_bwd(C.byref(both), *([0x1000] * 10), None) == P.E_UNSUPPORTED
+    assert lib.loong_attn_step_bwd(C.byref(both), *([0x1000] * 10), None, 0, None) == P.E_UNSUPPORTED
     z = _good(batch=0, flags=P.BWD_ONLY_DKV)
-    assert lib.loong_attn_step_bwd(C.byref(z), 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, None) == P.OK
-    assert lib.loong_attn_step_bwd(C.byref(z), 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, None, None, 0x1000, None) == P.E_NULL
+    assert lib.loong_attn_step_bwd(C.byref(z), 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, None, 0, None) == P.OK
+    assert lib.loong_attn_step_bwd(C.byref(z), 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, None, None, 0x1000, None, 0, None) == P.E_NULL
     z = _good(batch=0, flags=P.BWD_ONLY_DQ)
-    assert lib.loong_attn_step_bwd(C.byref(z), 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, 0x1000, None, None, None) == P.OK
-    assert lib.loong_attn_step_bwd(C.byref(z), 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, None, None, None, None) == P.E_NULL
+    assert lib.loong_attn_step_bwd(C.byref(z), 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, 0x1000, None, None, None, 0, None) == P.OK
+    assert lib.loong_attn_step_bwd(C.byref(z), 0x1000, 0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, None, None, None, None, 0, None) == P.E_NULL
 
 
 def test_error_text_is_per_call():
@@ -144,16 +144,16 @@ def test_layout_and_probe_entry_points_validate_before_touching_a_device():
     assert lib.loong_reduce_replicas(2, 2, 6, 0x1000, 0x2000, None) == P.E_ALIGN
     assert lib.loong_reduce_replicas(0, 2, 4, 0x1000, 0x2000, None) == P.OK
     assert lib.loong_mfma_probe(0, 1, 0x1000, None) == P.E_SHAPE
-    assert lib.loong_reserve_workspace(-1) == P.E_SHAPE and lib.loong_reserve_workspace(1 << 40) == P.E_SHAPE
     assert lib.loong_mfma_probe(1, 1, None, None) == P.E_NULL
 
 
 def test_workspace_bytes_follows_the_split_of_the_query_loops():
     """Few key tiles (fewer than CUs): the query loops are shared and partial sums are parked; many: nothing is."""
     per_item = 8 * (128 // 32) * 16 * 64 * 4            # one (key tile, split) slot: eight waves' accumulators
+    counters = 16384 * 4                                 # the arrival counters in front of the partial sums
     small = _good(n_q_heads=8, n_kv_heads=8, q_len=4096, kv_len=4096, chunk_len=2048, causal=1,
                   q_chunk=(7, 8), kv_chunk=(3, 12))      # both local chunks see the early key chunk only: 16 tiles x 8 heads
-    assert P.workspace_bytes(small) == 128 * 2 * per_item
+    assert P.workspace_bytes(small) == counters + 128 * 2 * per_item
     big = _good(n_q_heads=8, n_kv_heads=8, q_len=16384, kv_len=16384, chunk_len=8192, causal=1,
                 q_chunk=(0, 31), kv_chunk=(5, 26))
     assert P.workspace_bytes(big) == 0
@@ -164,6 +164,33 @@ def test_workspace_bytes_follows_the_split_of_the_query_loops():
     lib = P.binding.lib
     import ctypes as C
     assert lib.loong_workspace_bytes(C.byref(small), None) == P.E_NULL
+
+
+def test_backward_step_rejects_a_missing_or_small_workspace_before_any_launch():
+    """The step that shares query loops needs caller-owned scratch: without it, or with too little or a misaligned
+    block, the call returns an argument error and enqueues nothing (fake addresses are never dereferenced)."""
+    import ctypes as C
+    lib = P.binding.lib
+    small = _good(n_q_heads=8, n_kv_heads=8, q_len=4096, kv_len=4096, chunk_len=2048, causal=1,
+                  q_chunk=(7, 8), kv_chunk=(3, 12))
+    need = P.workspace_bytes(small)
+    assert need > 0
+    ptrs = [0x1000] * 3 + [None] + [0x1000] * 6
+    assert lib.loong_attn_step_bwd(C.byref(small), *ptrs, None, 0, None) == P.E_NULL and "workspace" in P.last_error()
+    assert lib.loong_attn_step_bwd(C.byref(small), *ptrs, 0x1000, need - 1, None) == P.E_SHAPE and str(need) in P.last_error()
+    assert lib.loong_attn_step_bwd(C.byref(small), *ptrs, 0x1008, need, None) == P.E_ALIGN
+    assert lib.loong_attn_step_bwd(C.byref(small), *ptrs, 0x1000, -1, None) == P.E_SHAPE
+    # the dQ half alone needs none
+    small.flags = P.BWD_ONLY_DQ
+    assert P.workspace_bytes(small) == 0
+
+
+def test_key_split_override_is_validated():
+    assert P.validate_step(_good(flags=P.key_splits(1))) == P.OK
+    assert P.validate_step(_good(flags=P.key_splits(2) | P.FUSE_MERGE)) == P.OK
+    assert P.validate_step(_good(flags=P.key_splits(4))) == P.OK
+    for bad in (3, 5, 6, 7):
+        assert P.validate_step(_good(flags=P.key_splits(bad))) == P.E_UNSUPPORTED and "LOONG_KEY_SPLITS" in P.last_error()
 
 
 def test_bench_refuses_more_than_one_gpu():
