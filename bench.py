@@ -5,15 +5,17 @@ One "step" is one pass of the whole hot path for the simulated rank: cp x (step 
 fused with Update) + cast to the stored activation type + delta + cp x step backward,
 every K/V chunk resident in HBM, launches back to back on one stream.
 
-Prints ONE JSON line: fwd+bwd TFLOP/s (14*d FLOP per visible (query, key) pair per q
-head: 4d forward, 10d backward including the recomputation the method needs), the MFMA
-roofline of the dominant kernel (the dK/dV kernel of the backward step, timed with events
-around a rotating sample of its launches inside the timed region: every event costs a few
-microseconds of stream time, so bracketing all launches would slow the pass by ~4 %), and
-the fp64 oracle timed on the host cores on a bounded sample of the same workload.  Extras,
+The default workload is the largest one-GPU shape (the 1M-token shard); --config picks
+another.  Prints ONE JSON line: fwd+bwd TFLOP/s (14*d FLOP per visible (query, key) pair
+per q head: 4d forward, 10d backward including the recomputation the method needs), the
+MFMA roofline of the dominant kernel (the dK/dV kernel of the backward step, timed with
+events around a rotating sample of its launches inside the timed region: every event costs
+a few microseconds of stream time, so bracketing all launches would slow the pass), and the
+fp64 oracle timed on the host cores on a bounded sample of the same workload.  Extras,
 measured after the timed region: every kernel bracketed, the pass replayed from a captured
-graph, the step classes, Update alone, the two-buffer replay, the layout steps, the matrix
-cores alone.
+graph, the step classes, Update alone, the two-buffer replay against the performance model
+fed with the measured step and copy times, the model's best grid for the paper's 64-GPU
+setting, the layout steps, the matrix cores alone, and short runs of the other 7B shapes.
 """
 from __future__ import annotations
 
@@ -28,11 +30,17 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this script (summaries under profiles/), scaled by the same counters' reading for a copy kernel
-# of known size; null for workloads that were not profiled.
-TRAFFIC: dict = {"mha7b_32k": 77.7e6}  # 34.1 MiB read + 40.0 MiB written per bwd_dkv launch (average of the eight steps)
+# HBM bytes per launch of the dominant kernel (average over the micro-steps of a pass) from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (summaries under profiles/), scaled
+# by the same counters' reading for a copy kernel of known size; null for workloads not profiled.
+TRAFFIC: dict = {
+    "mha7b_32k": 77.7e6,   # 34.1 MiB read + 40.0 MiB written
+}
+
+# model dimensions behind the local shapes (LLaMA2-7B: hidden 4096, 32 heads; 8 kv heads for GQA)
+MODEL_D, MODEL_H = 4096, 32
 
 
 def pairs_per_head(cfg) -> int:
@@ -62,18 +70,132 @@ def cpu_baseline(cfg, inp, budget_rows: int):
     orc.attention_backward(inp["q"][:, rows], inp["k_all"], inp["v_all"], inp["d_out"][:, rows], pos_q, pos_k, cfg.scale)
     dt = time.perf_counter() - t0
     pairs = int((pos_q + 1).sum()) * cfg.hq
-    return {
-        "value": 14.0 * cfg.d * pairs / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-        "sample": f"{len(rows)} of {cfg.L} local rows x {cfg.hq} heads x all {cfg.S} keys, fwd+bwd, {dt:.1f} s",
-    }
+    rate = 14.0 * cfg.d * pairs / dt / 1e12
+    whole = 14.0 * cfg.d * pairs_per_head(cfg) * cfg.hq / 1e12 / rate
+    sample = f"{len(rows)} of {cfg.L} local rows x {cfg.hq} heads x all {cfg.S} keys, fwd+bwd, {dt:.1f} s"
+    if len(rows) < cfg.L:
+        sample += f"; the whole workload at this rate: {whole:.0f} s (extrapolated)"
+    return {"value": rate, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle", "sample": sample}
+
+
+class Bench:
+    """Device tensors, descriptors and the launch sequence of one workload."""
+
+    def __init__(self, cfg, fuse=True):
+        import torch
+        import paper_2406_18485_amd as P
+        from gpu_harness import Replayed
+        from workloads import make_inputs
+        self.torch, self.P, self.cfg, self.fuse = torch, P, cfg, fuse
+        self.inp = make_inputs(cfg)
+        self.run = Replayed(cfg, self.inp)
+        self.rep, s = self.run.rep, self.run.rep.shape
+        self.desc0 = P.make_desc(batch=1, n_q_heads=s.hq, n_kv_heads=s.hkv, head_dim=s.d, q_len=s.L, kv_len=s.L,
+                                 dtype=s.dtype, softmax_scale=s.scale)
+        self.step_desc = [P.make_desc(batch=1, n_q_heads=s.hq, n_kv_heads=s.hkv, head_dim=s.d, q_len=s.L, kv_len=s.L,
+                                      dtype=s.dtype, softmax_scale=s.scale, causal=True, chunk_len=s.c,
+                                      q_chunk=st["q_chunk"], kv_chunk=st["kv_chunk"]) for st in self.rep.plan]
+        self.pairs = pairs_per_head(cfg) * cfg.hq
+
+    def event(self):
+        return self.torch.cuda.Event(enable_timing=True)
+
+    def backward_step(self, i, flags):
+        P, run, rep = self.P, self.run, self.rep
+        src = rep.plan[i]["src_rank"]
+        d = self.step_desc[i]
+        d.flags = flags
+        P.attn_step_bwd(d, run.q, run.k_by_src[src], run.v_by_src[src], None, run.d_o, rep.lse, rep.delta,
+                        None if flags & P.BWD_ONLY_DKV else rep.dq,
+                        None if flags & P.BWD_ONLY_DQ else rep.dk[src], None if flags & P.BWD_ONLY_DQ else rep.dv[src],
+                        rep.workspace)
+
+    def one_pass(self, sampled=(), every=None):
+        """One pass of the path.  `sampled`: {step: (ev0, ev1)} brackets the dK/dV kernel of those
+        backward micro-steps with events (the step is then issued as its two halves); `every`: an event
+        dictionary that brackets the forward replay and both halves of every backward micro-step."""
+        P, run, rep = self.P, self.run, self.rep
+        if every:
+            every["fwd0"].record()
+        rep.forward(run.q, run.k_by_src, run.v_by_src, fuse_merge=self.fuse)
+        if every:
+            every["fwd1"].record()
+        P.bwd_delta(self.desc0, rep.o, run.d_o, rep.delta)
+        rep.dq.zero_()
+        for i in range(self.cfg.cp):
+            if every:
+                every["bwd"][i][0].record()
+                self.backward_step(i, P.BWD_ONLY_DKV)
+                every["bwd"][i][1].record()
+                self.backward_step(i, P.BWD_ONLY_DQ)
+                every["bwd"][i][2].record()
+            elif i in sampled:
+                sampled[i][0].record()
+                self.backward_step(i, P.BWD_ONLY_DKV)
+                sampled[i][1].record()
+                self.backward_step(i, P.BWD_ONLY_DQ)
+            else:
+                self.backward_step(i, 0)
+
+    def timed_passes(self, steps, warmup):
+        """`warmup` untimed passes, then `steps` timed ones with the dominant kernel bracketed on a rotating
+        sample of the micro-steps: pass p times the dK/dV kernel of the steps i with i = p (mod max(steps, cp))
+        folded onto the steps, so that every step is sampled equally often (when steps is a multiple of cp, or
+        smaller than cp).  Returns (seconds per pass, average dK/dV launch in ms, timed launches)."""
+        torch, cp = self.torch, self.cfg.cp
+
+        def sample_of(pass_no):
+            if steps >= cp:
+                return [pass_no % cp]
+            return [i for i in range(cp) if i % steps == pass_no % steps]
+
+        for _ in range(warmup):
+            self.one_pass()
+        torch.cuda.synchronize()
+        samples = [{i: (self.event(), self.event()) for i in sample_of(pno)} for pno in range(steps)]
+        t0 = time.perf_counter()
+        for pno in range(steps):
+            self.one_pass(sampled=samples[pno])
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        per_step = {}
+        for smp in samples:
+            for i, (a, b) in smp.items():
+                per_step.setdefault(i, []).append(a.elapsed_time(b))
+        # mean over the micro-steps of the mean of each step's samples (steps never sampled, possible only
+        # when --steps is smaller than cp would need, are left out of the mean)
+        dkv_launch_ms = sum(sum(v) / len(v) for v in per_step.values()) / len(per_step)
+        return dt / steps, dkv_launch_ms, sum(len(v) for v in per_step.values()), len(per_step)
+
+    def roofline(self, dkv_launch_ms, timed_launches, steps_seen):
+        cfg = self.cfg
+        flop_per_launch = 8.0 * cfg.d * self.pairs / cfg.cp
+        achieved = flop_per_launch / (dkv_launch_ms * 1e-3) / 1e12
+        return {"bound": "mfma", "kernel": "bwd_dkv_kernel (dK/dV half of one backward micro-step)",
+                "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": TRAFFIC.get(cfg.name),
+                "avg_launch_ms": round(dkv_launch_ms, 4), "launches_per_step": cfg.cp,
+                "timed_launches": timed_launches, "micro_steps_sampled": steps_seen,
+                "flop_per_launch": round(flop_per_launch)}
+
+
+def settle_clock(P, torch, seconds=0.35):
+    """The shader clock climbs from idle for about 0.3 s under load: run the matrix-core probe for that long
+    before anything is timed, so that a short warm-up does not read a few per cent low."""
+    sink = torch.empty(2048 * 256, device="cuda:0")
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        P.mfma_probe(2048, 2000, sink)
+        torch.cuda.synchronize()
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None, help="timed passes (default: 200 for the 32K shape, fewer for the long ones)")
-    ap.add_argument("--warmup", type=int, default=None, help="untimed passes before them (default: as many as --steps' default: the clock needs ~0.3 s of load to settle)")
-    ap.add_argument("--config", type=int, default=1, help="index into workloads.CONFIGS (1 = 7B MHA shard, 32K)")
+    ap.add_argument("--steps", type=int, default=None, help="timed passes (default: 8 for the 1M-token shape, more for the shorter ones)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed passes before them (default: 2..20 by workload; the clock is "
+                                                              "settled by a 0.35 s matrix-core load before them in any case)")
+    ap.add_argument("--config", type=int, default=4, help="index into workloads.CONFIGS (4 = the 1M-token shard, the largest one-GPU shape)")
     ap.add_argument("--cpu-rows", type=int, default=-1,
                     help="rows of the oracle sample (0: skip the CPU baseline; -1: sized for about 15 s of host work)")
     ap.add_argument("--unfused", action="store_true", help="run Attention and Update as separate kernels")
@@ -83,6 +205,8 @@ def main():
     ap.add_argument("--dtype", choices=["bf16", "fp16"], default=None,
                     help="storage type of q, k, v, o, d_o (default: the workload's, bf16); fp16 runs the same kernels "
                          "with the fp16 matrix instruction (same 2.5 PFLOP/s peak)")
+    ap.add_argument("--no-extras", action="store_true", help="skip everything after the timed region except the CPU baseline")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the short runs of the other 7B shapes")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="launch only device-to-device copies of 256 MiB (reference for the HBM byte counters) and exit")
     args = ap.parse_args()
@@ -92,17 +216,14 @@ def main():
 
     import torch
     import paper_2406_18485_amd as P
-    from gpu_harness import Replayed
-    from workloads import CONFIGS, make_inputs
+    from workloads import CONFIGS
 
     cfg = CONFIGS[args.config]
-    # default pass counts: about 0.3 s of load before the timed region (the clock climbs from idle
-    # for that long; 10 warm-up passes of the 32K shape read 1 % low), about as much inside it
-    passes = {0: 200, 1: 200, 2: 32, 3: 10, 4: 4}.get(args.config, 10)
+    default_passes = {0: (200, 20), 1: (200, 20), 2: (32, 8), 3: (10, 3), 4: (8, 2)}.get(args.config, (10, 3))
     if args.steps is None:
-        args.steps = passes
+        args.steps = default_passes[0]
     if args.warmup is None:
-        args.warmup = passes
+        args.warmup = default_passes[1]
     if args.rank is not None:
         if not 0 <= args.rank < cfg.cp:
             sys.exit(f"--rank must be in [0, {cfg.cp})")
@@ -121,199 +242,16 @@ def main():
         print(json.dumps({"copy_calibration": {"bytes_read_per_launch": src.numel() * 4,
                                                "bytes_written_per_launch": src.numel() * 4, "launches": 8}}))
         return
-    inp = make_inputs(cfg)
-    run = Replayed(cfg, inp)
-    rep, s = run.rep, run.rep.shape
-    fuse = not args.unfused
 
-    desc0 = P.make_desc(batch=1, n_q_heads=s.hq, n_kv_heads=s.hkv, head_dim=s.d, q_len=s.L, kv_len=s.L,
-                        dtype=s.dtype, softmax_scale=s.scale)
-    step_desc = [P.make_desc(batch=1, n_q_heads=s.hq, n_kv_heads=s.hkv, head_dim=s.d, q_len=s.L, kv_len=s.L,
-                             dtype=s.dtype, softmax_scale=s.scale, causal=True, chunk_len=s.c,
-                             q_chunk=st["q_chunk"], kv_chunk=st["kv_chunk"]) for st in rep.plan]
-    E = lambda: torch.cuda.Event(enable_timing=True)
+    bench = Bench(cfg, fuse=not args.unfused)
+    run, rep = bench.run, bench.rep
+    pairs = bench.pairs
+    E = bench.event
 
-    def backward_step(i, flags):
-        src = rep.plan[i]["src_rank"]
-        d = step_desc[i]
-        d.flags = flags
-        P.attn_step_bwd(d, run.q, run.k_by_src[src], run.v_by_src[src], None, run.d_o, rep.lse, rep.delta,
-                        None if flags & P.BWD_ONLY_DKV else rep.dq,
-                        None if flags & P.BWD_ONLY_DQ else rep.dk[src], None if flags & P.BWD_ONLY_DQ else rep.dv[src],
-                        rep.workspace)
-
-    def one_pass(sampled=(), every=None):
-        """One pass of the path.  `sampled`: {step: (ev0, ev1)} brackets the dK/dV kernel of those
-        backward micro-steps with events (the step is then issued as its two halves); `every`: an event
-        dictionary that brackets the forward replay and both halves of every backward micro-step."""
-        if every:
-            every["fwd0"].record()
-        rep.forward(run.q, run.k_by_src, run.v_by_src, fuse_merge=fuse)
-        if every:
-            every["fwd1"].record()
-        P.bwd_delta(desc0, rep.o, run.d_o, rep.delta)
-        rep.dq.zero_()
-        for i in range(cfg.cp):
-            if every:
-                every["bwd"][i][0].record()
-                backward_step(i, P.BWD_ONLY_DKV)
-                every["bwd"][i][1].record()
-                backward_step(i, P.BWD_ONLY_DQ)
-                every["bwd"][i][2].record()
-            elif i in sampled:
-                sampled[i][0].record()
-                backward_step(i, P.BWD_ONLY_DKV)
-                sampled[i][1].record()
-                backward_step(i, P.BWD_ONLY_DQ)
-            else:
-                backward_step(i, 0)
-
-    # Every event costs a gap of a few microseconds on the stream, so the timed region brackets only
-    # the dominant kernel, and only on a rotating sample of the micro-steps: pass p times the
-    # dK/dV kernel of the steps i with i = p (mod max(steps, cp)) folded onto the steps, so that every step
-    # is sampled equally often (when steps is a multiple of cp, or smaller than cp).
-    def sample_of(pass_no):
-        if args.steps >= cfg.cp:
-            return [pass_no % cfg.cp]
-        return [i for i in range(cfg.cp) if i % args.steps == pass_no % args.steps]
-
-    for _ in range(args.warmup):
-        one_pass()
-    torch.cuda.synchronize()
-    samples = [{i: (E(), E()) for i in sample_of(pno)} for pno in range(args.steps)]
-    t0 = time.perf_counter()
-    for pno in range(args.steps):
-        one_pass(sampled=samples[pno])
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-
-    ms_per_step = dt / args.steps * 1e3
-    pairs = pairs_per_head(cfg) * cfg.hq
-    tflops = 14.0 * cfg.d * pairs / (dt / args.steps) / 1e12
-    # dominant kernel: the dK/dV kernel of the backward micro-step.  Its algorithmic work is four of
-    # the backward's five matrix products (S, dP, dV, dK): 8*d FLOP per visible pair.  Average launch
-    # duration: mean over the micro-steps of the mean of each step's samples.
-    per_step = {}
-    for smp in samples:
-        for i, (a, b) in smp.items():
-            per_step.setdefault(i, []).append(a.elapsed_time(b))
-    assert len(per_step) == cfg.cp, "every micro-step must have been sampled"
-    dkv_launch_ms = sum(sum(v) / len(v) for v in per_step.values()) / cfg.cp
-    dkv_ms = dkv_launch_ms * cfg.cp
-    dkv_tflops = 8.0 * cfg.d * pairs / (dkv_ms * 1e-3) / 1e12
-
-    # ---- every kernel bracketed (costs ~4 % of the pass: measured outside the timed region) ----------
-    def new_events():
-        return {"fwd0": E(), "fwd1": E(), "bwd": [(E(), E(), E()) for _ in rep.plan]}
-    n_inst = 3
-    events = [new_events() for _ in range(n_inst)]
-    t1 = time.perf_counter()
-    for ev in events:
-        one_pass(every=ev)
-    torch.cuda.synchronize()
-    instrumented_ms = (time.perf_counter() - t1) / n_inst * 1e3
-    fwd_ms = sum(e["fwd0"].elapsed_time(e["fwd1"]) for e in events) / n_inst
-    dkv_all_ms = sum(a.elapsed_time(b) for e in events for a, b, _ in e["bwd"]) / n_inst
-    dq_ms = sum(b.elapsed_time(c) for e in events for _, b, c in e["bwd"]) / n_inst
-    bwd_ms = dkv_all_ms + dq_ms
-    per_kernel = {
-        "note": f"every launch bracketed with events in {n_inst} extra passes after the timed region "
-                f"({round(instrumented_ms, 4)} ms per such pass)",
-        "fwd_kernel": {"flop_per_pair": "4*d", "avg_launch_ms": round(fwd_ms / cfg.cp, 4),
-                       "tflops": round(4.0 * cfg.d * pairs / (fwd_ms * 1e-3) / 1e12, 1)},
-        "bwd_dkv_kernel": {"flop_per_pair": "8*d", "avg_launch_ms": round(dkv_all_ms / cfg.cp, 4),
-                           "tflops": round(8.0 * cfg.d * pairs / (dkv_all_ms * 1e-3) / 1e12, 1)},
-        "dq_kernel": {"flop_per_pair": "6*d (S and dP recomputed)", "avg_launch_ms": round(dq_ms / cfg.cp, 4),
-                      "tflops": round(6.0 * cfg.d * pairs / (dq_ms * 1e-3) / 1e12, 1)},
-    }
-    # the same pass replayed from a captured graph (no host launches; extra, never `value`)
-    graph_ms = None
-    try:
-        side = torch.cuda.Stream()
-        with torch.cuda.stream(side):
-            one_pass()
-            torch.cuda.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=side):
-                one_pass()
-        torch.cuda.synchronize()
-        g.replay()
-        torch.cuda.synchronize()
-        t2 = time.perf_counter()
-        for _ in range(args.steps):
-            g.replay()
-        torch.cuda.synchronize()
-        graph_ms = round((time.perf_counter() - t2) / args.steps * 1e3, 4)
-    except Exception as exc:  # a capture failure must not cost the benchmark line
-        graph_ms = f"capture failed: {exc}"
-    # ---- extra figures, measured after the timed region ------------------------------------
-    def timed(fn, reps):
-        fn()
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(reps):
-            fn()
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps
-
-    # per step class (rank 0: step 0 holds the own chunk = the diagonal step, the others two FULL blocks)
-    def cls_ms(sel):
-        idx = [i for i, st in enumerate(rep.plan) if sel(st)]
-        if not idx:
-            return None
-        tot = sum(e["bwd"][i][0].elapsed_time(e["bwd"][i][2]) for e in events for i in idx)
-        return round(tot / (len(idx) * n_inst), 4)
-    step_classes = {"bwd_ms_diagonal_step": cls_ms(lambda st: st["src_rank"] == cfg.rank),
-                    "bwd_ms_other_steps": cls_ms(lambda st: st["src_rank"] != cfg.rank)}
-    # Update as a kernel of its own (HBM-bound): 3 x 4 x d + 3 x 4 bytes per merged row
-    rows = cfg.hq * cfg.L
-    blk_out, blk_lse = torch.randn(rows, cfg.d, device="cuda:0"), torch.randn(rows, device="cuda:0")
-    run_out, run_lse = torch.randn(rows, cfg.d, device="cuda:0"), torch.randn(rows, device="cuda:0")
-    merge_ms = timed(lambda: P.lse_merge(rows, cfg.d, run_out, run_lse, blk_out, blk_lse), 20)
-    merge = {"rows": rows, "ms": round(merge_ms, 4), "bytes_per_row": 12 * cfg.d + 12,
-             "GB_per_s": round(rows * (12 * cfg.d + 12) / (merge_ms * 1e-3) / 1e9, 1), "hbm_peak_GB_per_s": 8000}
-    # forward with the receive buffers of Alg. 2 (device-to-device copies on two side streams stand in
-    # for the inner- and outer-ring transfers) against the forward over resident chunks
-    fwd_resident_ms = timed(lambda: rep.forward(run.q, run.k_by_src, run.v_by_src), 5)
-    fwd_buffers_ms = timed(lambda: rep.forward_two_buffers(run.q, run.k_by_src, run.v_by_src), 5)
-    stage_k = torch.empty_like(run.k_by_src[0])
-    stage_v = torch.empty_like(run.v_by_src[0])
-    def copies():
-        for st in rep.plan:
-            stage_k.copy_(run.k_by_src[st["src_rank"]], non_blocking=True)
-            stage_v.copy_(run.v_by_src[st["src_rank"]], non_blocking=True)
-    copies_ms = timed(copies, 5)
-    two_buffers = {"fwd_ms_resident": round(fwd_resident_ms, 4), "fwd_ms_two_buffers": round(fwd_buffers_ms, 4),
-                   "copies_alone_ms": round(copies_ms, 4),
-                   "exposed_transfer_ms": round(max(0.0, fwd_buffers_ms - fwd_resident_ms), 4),
-                   "chunk_MiB": round(run.k_by_src[0].numel() * run.k_by_src.element_size() * 2 / 2**20, 1)}
-    # layout steps either side of the ring (HBM-bound, every byte read once and written once):
-    # 32 heads x 4096 tokens x 128 bf16 into 4 head-group messages and back into the ring layout,
-    # and the gradient reduction of 4-fold replicated KV heads
-    s_tok, Hh, dd, hp = 4096, 32, 128, 4
-    hl = Hh // hp
-    xin = torch.zeros(s_tok, Hh, dd, dtype=torch.bfloat16, device="cuda:0")
-    msg = torch.zeros(hp, hl, s_tok, dd, dtype=torch.bfloat16, device="cuda:0")
-    loc = torch.zeros(hl, hp * s_tok, dd, dtype=torch.bfloat16, device="cuda:0")
-    nbytes = xin.numel() * 2
-    pack_ms = timed(lambda: P.permute_rows((hp, hl, s_tok), (hl * dd * 2, dd * 2, Hh * dd * 2),
-                                           (hl * s_tok * dd * 2, s_tok * dd * 2, dd * 2), dd * 2, xin, msg), 20)
-    unpack_ms = timed(lambda: P.permute_rows((hp, hl, s_tok), (hl * s_tok * dd * 2, s_tok * dd * 2, dd * 2),
-                                             (s_tok * dd * 2, hp * s_tok * dd * 2, dd * 2), dd * 2, msg, loc), 20)
-    gin = torch.zeros(8 * 4, s_tok * dd, device="cuda:0")
-    gout = torch.zeros(8, s_tok * dd, device="cuda:0")
-    red_ms = timed(lambda: P.reduce_replicas(8, 4, s_tok * dd, gin, gout), 20)
-    layout = {"pack_heads_GB_per_s": round(2 * nbytes / (pack_ms * 1e-3) / 1e9, 1),
-              "unpack_tokens_GB_per_s": round(2 * nbytes / (unpack_ms * 1e-3) / 1e9, 1),
-              "reduce_replicas_GB_per_s": round((gin.numel() + gout.numel()) * 4 / (red_ms * 1e-3) / 1e9, 1),
-              "tensor_MiB": nbytes >> 20}
-    # the matrix cores alone, at the clocks the chip really holds
-    wgs, iters_probe = 256 * 8, 4000
-    sink = torch.empty(wgs * 256, device="cuda:0")
-    probe_ms = timed(lambda: P.mfma_probe(wgs, iters_probe, sink), 3)
-    mfma_sustained = wgs * 4 * iters_probe * 4 * 32768 / (probe_ms * 1e-3) / 1e12
+    settle_clock(P, torch)
+    sec_per_pass, dkv_launch_ms, timed_launches, steps_seen = bench.timed_passes(args.steps, args.warmup)
+    ms_per_step = sec_per_pass * 1e3
+    tflops = 14.0 * cfg.d * pairs / sec_per_pass / 1e12
 
     result = {
         "metric": "fwd+bwd ring-step attention TFLOP/s on 1 GPU; % of bf16 MFMA peak",
@@ -322,29 +260,191 @@ def main():
         "dtype": {"bf16": "bf16", "fp16": "f16", "fp32": "f32"}[cfg.dtype], "data": "synthetic",
         "config": {"workload": cfg.name, "cp": cfg.cp, "inner_ring": cfg.w, "rank": cfg.rank, "q_heads": cfg.hq,
                    "kv_heads": cfg.hkv, "head_dim": cfg.d, "local_tokens": cfg.L, "total_seq": cfg.S,
-                   "ring_steps": cfg.cp, "update": "fused" if fuse else "separate kernel",
+                   "ring_steps": cfg.cp, "update": "fused" if bench.fuse else "separate kernel",
                    "flop_convention": "14*d per visible pair per q head (4d fwd + 10d bwd)"},
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "tflops_12d_convention": round(tflops * 12.0 / 14.0, 2),
-        "roofline": {"bound": "mfma", "kernel": "bwd_dkv_kernel (dK/dV half of one backward micro-step)",
-                     "achieved": round(dkv_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(dkv_tflops / PEAK_BF16_TFLOPS, 4), "traffic": TRAFFIC.get(cfg.name),
-                     "avg_launch_ms": round(dkv_launch_ms, 4), "launches_per_step": cfg.cp,
-                     "timed_launches": sum(len(v) for v in per_step.values()),
-                     "flop_per_launch": round(8.0 * cfg.d * pairs / cfg.cp)},
-        "kernels": per_kernel,
-        "graph_replay_ms_per_step": graph_ms,
-        "step_classes": step_classes,
-        "merge_only": merge,
-        "layout_steps": layout,
-        "two_buffer_replay": two_buffers,
-        "mfma_only_probe_tflops": round(mfma_sustained, 1),
-        "pct_of_mfma_only_probe": round(100.0 * tflops / mfma_sustained, 2),
-        "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
+        "roofline": bench.roofline(dkv_launch_ms, timed_launches, steps_seen),
     }
+
+    if not args.no_extras:
+        # ---- every kernel bracketed (costs a few % of the pass: measured outside the timed region) ------
+        def new_events():
+            return {"fwd0": E(), "fwd1": E(), "bwd": [(E(), E(), E()) for _ in rep.plan]}
+        n_inst = 3
+        events = [new_events() for _ in range(n_inst)]
+        t1 = time.perf_counter()
+        for ev in events:
+            bench.one_pass(every=ev)
+        torch.cuda.synchronize()
+        instrumented_ms = (time.perf_counter() - t1) / n_inst * 1e3
+        fwd_ms = sum(e["fwd0"].elapsed_time(e["fwd1"]) for e in events) / n_inst
+        dkv_all_ms = sum(a.elapsed_time(b) for e in events for a, b, _ in e["bwd"]) / n_inst
+        dq_ms = sum(b.elapsed_time(c) for e in events for _, b, c in e["bwd"]) / n_inst
+        bwd_ms = dkv_all_ms + dq_ms
+        tf = lambda flop_per_pair_over_d, ms: round(flop_per_pair_over_d * cfg.d * pairs / (ms * 1e-3) / 1e12, 1)
+        result["kernels"] = {
+            "note": f"every launch bracketed with events in {n_inst} extra passes after the timed region "
+                    f"({round(instrumented_ms, 4)} ms per such pass); 'algorithmic' counts each of the method's "
+                    "seven matrix products once (4d forward, 10d backward), 'executed' what the kernel really issues",
+            "fwd_kernel": {"algorithmic_flop_per_pair": "4*d", "avg_launch_ms": round(fwd_ms / cfg.cp, 4),
+                           "tflops": tf(4.0, fwd_ms)},
+            "bwd_dkv_kernel": {"algorithmic_flop_per_pair": "8*d (S, dP, dV, dK)", "avg_launch_ms": round(dkv_all_ms / cfg.cp, 4),
+                               "tflops": tf(8.0, dkv_all_ms)},
+            "dq_kernel": {"algorithmic_flop_per_pair": "2*d (dQ; S and dP are already counted in the dK/dV kernel)",
+                          "executed_flop_per_pair": "6*d (S and dP recomputed)", "avg_launch_ms": round(dq_ms / cfg.cp, 4),
+                          "tflops_algorithmic": tf(2.0, dq_ms), "tflops_executed": tf(6.0, dq_ms)},
+            "backward_both_kernels": {"algorithmic_flop_per_pair": "10*d", "executed_flop_per_pair": "14*d",
+                                      "tflops_algorithmic": tf(10.0, bwd_ms), "tflops_executed": tf(14.0, bwd_ms)},
+        }
+        result["fwd_ms"], result["bwd_ms"] = round(fwd_ms, 4), round(bwd_ms, 4)
+        # the same pass replayed from a captured graph (no host launches; extra, never `value`)
+        try:
+            side = torch.cuda.Stream()
+            with torch.cuda.stream(side):
+                bench.one_pass()
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    bench.one_pass()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            for _ in range(args.steps):
+                g.replay()
+            torch.cuda.synchronize()
+            result["graph_replay_ms_per_step"] = round((time.perf_counter() - t2) / args.steps * 1e3, 4)
+        except Exception as exc:  # a capture failure must not cost the benchmark line
+            result["graph_replay_ms_per_step"] = f"capture failed: {exc}"
+
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            a, b = E(), E()
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+
+        # per step class (rank 0: step 0 holds the own chunk = the diagonal step, the others two FULL blocks)
+        def cls_ms(sel):
+            idx = [i for i, st in enumerate(rep.plan) if sel(st)]
+            if not idx:
+                return None
+            tot = sum(e["bwd"][i][0].elapsed_time(e["bwd"][i][2]) for e in events for i in idx)
+            return round(tot / (len(idx) * n_inst), 4)
+        result["step_classes"] = {"bwd_ms_diagonal_step": cls_ms(lambda st: st["src_rank"] == cfg.rank),
+                                  "bwd_ms_earlier_sources": cls_ms(lambda st: st["src_rank"] < cfg.rank),
+                                  "bwd_ms_later_sources": cls_ms(lambda st: st["src_rank"] > cfg.rank)}
+        # Update as a kernel of its own (HBM-bound): 3 x 4 x d + 3 x 4 bytes per merged row
+        rows = cfg.hq * cfg.L
+        blk_out, blk_lse = torch.randn(rows, cfg.d, device="cuda:0"), torch.randn(rows, device="cuda:0")
+        run_out, run_lse = torch.randn(rows, cfg.d, device="cuda:0"), torch.randn(rows, device="cuda:0")
+        merge_ms = timed(lambda: P.lse_merge(rows, cfg.d, run_out, run_lse, blk_out, blk_lse), 20)
+        merge_gbs = rows * (12 * cfg.d + 12) / (merge_ms * 1e-3) / 1e9
+        result["merge_only"] = {"rows": rows, "ms": round(merge_ms, 4), "bytes_per_row": 12 * cfg.d + 12,
+                                "GB_per_s": round(merge_gbs, 1), "hbm_peak_GB_per_s": HBM_PEAK_GBS,
+                                "frac_of_hbm_peak": round(merge_gbs / HBM_PEAK_GBS, 3)}
+        del blk_out, blk_lse, run_out, run_lse
+        # ---- forward with the receive buffers of Alg. 2 (device-to-device copies on two side streams stand in
+        # for the inner- and outer-ring transfers) against the forward over resident chunks, and against the
+        # performance model of Sec. "Performance Analysis" fed with what was just measured: alpha from the
+        # forward micro-step, the transfer bandwidth from the copies alone.
+        fwd_resident_ms = timed(lambda: rep.forward(run.q, run.k_by_src, run.v_by_src), 3)
+        fwd_buffers_ms = timed(lambda: rep.forward_two_buffers(run.q, run.k_by_src, run.v_by_src), 3)
+        stage_k = torch.empty_like(run.k_by_src[0])
+        stage_v = torch.empty_like(run.v_by_src[0])
+
+        def copies():
+            for st in rep.plan:
+                stage_k.copy_(run.k_by_src[st["src_rank"]], non_blocking=True)
+                stage_v.copy_(run.v_by_src[st["src_rank"]], non_blocking=True)
+        copies_ms = timed(copies, 3)
+        chunk_bytes = run.k_by_src[0].numel() * run.k_by_src.element_size() * 2
+        d_hp = MODEL_H // cfg.hq
+        d_sp = d_hp * cfg.cp
+        h_kv = MODEL_H if cfg.hkv == cfg.hq else 8
+        t_step = fwd_resident_ms * 1e-3 / cfg.cp
+        alpha = t_step * cfg.cp * d_sp / (float(cfg.S) ** 2 * MODEL_D)
+        bw_copy = chunk_bytes / (copies_ms * 1e-3 / cfg.cp)
+        model = P.cost_model(S=float(cfg.S), D=float(MODEL_D), H=MODEL_H, H_kv=h_kv, d_hp=d_hp, d_cp=cfg.cp, w=cfg.w,
+                             alpha_fwd=alpha, bw_p2p_inner=bw_copy, bw_p2p_outer=bw_copy, bw_alltoall=bw_copy, latency=0.0)
+        predicted_ms = model["t_inner_ring_fwd"] * (cfg.cp // cfg.w) * 1e3
+        result["two_buffer_replay"] = {
+            "fwd_ms_resident": round(fwd_resident_ms, 4), "fwd_ms_two_buffers": round(fwd_buffers_ms, 4),
+            "copies_alone_ms": round(copies_ms, 4), "chunk_MiB": round(chunk_bytes / 2**20, 1),
+            "exposed_transfer_ms_measured": round(max(0.0, fwd_buffers_ms - fwd_resident_ms), 4),
+            "model": {"formula": "forward = (d_cp / w) * (A (w - 1) + B), A = max(T_comp, T_p2p_inner), B = max(T_comp, T_p2p_outer)",
+                      "alpha_fwd_measured": alpha, "t_comp_fwd_ms": round(model["t_comp_fwd"] * 1e3, 4),
+                      "t_p2p_ms": round(model["t_p2p_inner_fwd"] * 1e3, 4), "size_kv_MiB": round(model["size_kv"] / 2**20, 2),
+                      "copy_GB_per_s": round(bw_copy / 1e9, 1), "fwd_ms_predicted": round(predicted_ms, 4),
+                      "exposed_transfer_ms_predicted": round(max(0.0, predicted_ms - fwd_resident_ms), 4)},
+        }
+        del stage_k, stage_v
+        # the model's best grid for the paper's setting (64 GPUs, 1M tokens, Sec. "Experiment Setup") on MI355X nodes,
+        # with this run's alpha and ASSUMED link rates: ring hop inside a node = one xGMI link, 76.8 GB/s per
+        # direction; between nodes one 400 Gb/s NIC per GPU = 50 GB/s; all-to-all inside a node = seven links
+        links = dict(bw_p2p_inner=76.8e9, bw_p2p_outer=50e9, bw_alltoall=7 * 76.8e9, latency=5e-6)
+        best = {}
+        for name, hkv in (("mha", 32), ("gqa", 8)):
+            b = P.cost_search(64, 8, S=float(1 << 20), D=float(MODEL_D), H=MODEL_H, H_kv=hkv, alpha_fwd=alpha, **links)
+            best[name] = {"d_hp": b["d_hp"], "d_cp": b["d_cp"], "w": b["w"], "objective_ms": round(b["objective"] * 1e3, 2),
+                          "t_seq_alltoall_ms": round(b["t_seq_alltoall"] * 1e3, 3)}
+        result["cost_model_best_grid_64gpu_1m"] = {"assumed_links": links, "alpha_fwd": alpha, **best}
+        # layout steps either side of the ring (HBM-bound, every byte read once and written once):
+        # 32 heads x 4096 tokens x 128 bf16 into 4 head-group messages and back into the ring layout,
+        # and the gradient reduction of 4-fold replicated KV heads
+        s_tok, Hh, dd, hp = 4096, 32, 128, 4
+        hl = Hh // hp
+        xin = torch.zeros(s_tok, Hh, dd, dtype=torch.bfloat16, device="cuda:0")
+        msg = torch.zeros(hp, hl, s_tok, dd, dtype=torch.bfloat16, device="cuda:0")
+        loc = torch.zeros(hl, hp * s_tok, dd, dtype=torch.bfloat16, device="cuda:0")
+        nbytes = xin.numel() * 2
+        pack_ms = timed(lambda: P.permute_rows((hp, hl, s_tok), (hl * dd * 2, dd * 2, Hh * dd * 2),
+                                               (hl * s_tok * dd * 2, s_tok * dd * 2, dd * 2), dd * 2, xin, msg), 20)
+        unpack_ms = timed(lambda: P.permute_rows((hp, hl, s_tok), (hl * s_tok * dd * 2, s_tok * dd * 2, dd * 2),
+                                                 (s_tok * dd * 2, hp * s_tok * dd * 2, dd * 2), dd * 2, msg, loc), 20)
+        gin = torch.zeros(8 * 4, s_tok * dd, device="cuda:0")
+        gout = torch.zeros(8, s_tok * dd, device="cuda:0")
+        red_ms = timed(lambda: P.reduce_replicas(8, 4, s_tok * dd, gin, gout), 20)
+        result["layout_steps"] = {"pack_heads_GB_per_s": round(2 * nbytes / (pack_ms * 1e-3) / 1e9, 1),
+                                  "unpack_tokens_GB_per_s": round(2 * nbytes / (unpack_ms * 1e-3) / 1e9, 1),
+                                  "reduce_replicas_GB_per_s": round((gin.numel() + gout.numel()) * 4 / (red_ms * 1e-3) / 1e9, 1),
+                                  "tensor_MiB": nbytes >> 20}
+        # the matrix cores alone, at the clocks the chip really holds
+        wgs, iters_probe = 256 * 8, 4000
+        sink = torch.empty(wgs * 256, device="cuda:0")
+        probe_ms = timed(lambda: P.mfma_probe(wgs, iters_probe, sink), 3)
+        mfma_sustained = wgs * 4 * iters_probe * 4 * 32768 / (probe_ms * 1e-3) / 1e12
+        result["mfma_only_probe_tflops"] = round(mfma_sustained, 1)
+        result["pct_of_mfma_only_probe"] = round(100.0 * tflops / mfma_sustained, 2)
+
     cpu_rows = auto_cpu_rows(cfg) if args.cpu_rows < 0 else args.cpu_rows
     if cpu_rows > 0:
-        result["cpu_baseline"] = cpu_baseline(cfg, inp, cpu_rows)
+        result["cpu_baseline"] = cpu_baseline(cfg, bench.inp, cpu_rows)
+
+    # ---- the other 7B shapes, briefly (about 0.3 s of timed passes each, same launch sequence, rank 0) ----
+    if not args.no_extras and not args.no_other_configs and args.rank is None and args.dtype is None and not args.unfused:
+        del bench, run, rep
+        torch.cuda.empty_cache()
+        others = {}
+        for idx, (steps, warmup) in ((1, (200, 20)), (2, (32, 4)), (3, (10, 2)), (4, (4, 1))):
+            if idx == args.config:
+                continue
+            ob = Bench(CONFIGS[idx])
+            settle_clock(P, torch, 0.2)
+            sec, launch_ms, n_timed, seen = ob.timed_passes(steps, warmup)
+            rate = 14.0 * ob.cfg.d * ob.pairs / sec / 1e12
+            roof = ob.roofline(launch_ms, n_timed, seen)
+            others[ob.cfg.name] = {"value": round(rate, 2), "pct_of_bf16_mfma_peak": round(100.0 * rate / PEAK_BF16_TFLOPS, 2),
+                                   "ms_per_step": round(sec * 1e3, 4), "steps": steps, "warmup": warmup,
+                                   "roofline_frac": roof["frac"], "dkv_avg_launch_ms": roof["avg_launch_ms"]}
+            del ob
+            torch.cuda.empty_cache()
+        result["per_config"] = others
     print(json.dumps(result), flush=True)
 
 

@@ -414,8 +414,12 @@ def test_rows_without_any_key_have_no_effect_on_the_backward():
     lse[:, blind] = -np.inf
     delta = ref[5].copy()
     delta[:, blind] = 0.0
-    dq_ref, dk_ref, dv_ref = orc.step_backward(q[0], k[0], v[0], do[0], lse, delta, np.zeros(nq, int), np.zeros(nk, int), scale, causal=False)
-    dq_ref[:, blind] = 0.0
+    # the oracle of "these rows take no part": the same backward with the blind rows left out
+    keep = ~blind
+    dq_keep, dk_ref, dv_ref = orc.step_backward(q[0][:, keep], k[0], v[0], do[0][:, keep], lse[:, keep], delta[:, keep],
+                                                np.zeros(keep.sum(), int), np.zeros(nk, int), scale, causal=False)
+    dq_ref = np.zeros((hq, nq, d))
+    dq_ref[:, keep] = dq_keep
     desc = P.make_desc(batch=b, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, q_len=nq, kv_len=nk, dtype=P.BF16, softmax_scale=scale)
     dq = torch.zeros(b, hq, nq, d, device=DEV)
     dk, dv = torch.empty(b, hkv, nk, d, device=DEV), torch.empty(b, hkv, nk, d, device=DEV)
