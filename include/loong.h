@@ -161,6 +161,24 @@ LOONG_API int loong_attn_step_bwd(const loong_step_desc* desc, const void* q, co
                         float* dq, float* dk, float* dv, void* workspace, int64_t workspace_bytes,
                         void* stream);
 
+/*
+ * loong_attn_step_bwd for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, semantics, results (bit for bit) and errors as loong_attn_step_bwd, except that
+ * the scratch of the dK/dV kernel is an array of LOONG_STATIC_SCRATCH_BYTES inside the library's
+ * device code (each GPU the library is used on holds its own copy until the process ends).
+ * The call allocates and frees nothing and does not synchronise.  A step that needs more
+ * scratch than the array holds (loong_workspace_bytes(desc) > LOONG_STATIC_SCRATCH_BYTES) is
+ * refused with LOONG_E_UNSUPPORTED and nothing is enqueued: use loong_attn_step_bwd.  All
+ * calls on one GPU share that GPU's array: calls that overlap on one GPU (two streams, two
+ * threads) race on it and must be ordered by the caller; the array keeps the last call's
+ * contents, and each call clears what it counts in on `stream` before its kernels use it.
+ */
+#define LOONG_STATIC_SCRATCH_BYTES (((int64_t)64 << 20) + 65536)
+LOONG_API int loong_attn_step_bwd_static(const loong_step_desc* desc, const void* q, const void* k, const void* v,
+                                         const void* o, const void* d_o, const float* lse, float* delta,
+                                         float* dq, float* dk, float* dv, void* stream);
+
 /* delta_i = sum_k d_o_ik * o_ik for every row; o, d_o in desc->dtype with q_stride. */
 LOONG_API int loong_bwd_delta(const loong_step_desc* desc, const void* o, const void* d_o, float* delta,
                     void* stream);

@@ -28,7 +28,7 @@ EXPORTS = (
     "loong_zigzag_mask", "loong_attn_step_fwd", "loong_lse_merge", "loong_attn_step_bwd",
     "loong_bwd_delta", "loong_init_running", "loong_finalize_out", "loong_validate_step",
     "loong_last_error", "loong_version", "loong_mfma_probe", "loong_cost_model", "loong_cost_search",
-    "loong_permute_rows", "loong_reduce_replicas", "loong_workspace_bytes",
+    "loong_permute_rows", "loong_reduce_replicas", "loong_workspace_bytes", "loong_attn_step_bwd_static",
 )
 
 
@@ -76,6 +76,7 @@ lib.loong_zigzag_mask.argtypes = [_i32, _i32, _i32, _i32, C.POINTER(_i32), C.POI
 lib.loong_attn_step_fwd.argtypes = [C.POINTER(StepDesc), _vp, _vp, _vp, _vp, _vp, _vp]
 lib.loong_lse_merge.argtypes = [_i64, _i32, _vp, _vp, _vp, _vp, _vp]
 lib.loong_attn_step_bwd.argtypes = [C.POINTER(StepDesc)] + [_vp] * 11 + [_i64, _vp]
+lib.loong_attn_step_bwd_static.argtypes = [C.POINTER(StepDesc)] + [_vp] * 11
 lib.loong_bwd_delta.argtypes = [C.POINTER(StepDesc), _vp, _vp, _vp, _vp]
 lib.loong_init_running.argtypes = [_i64, _i32, _vp, _vp, _vp]
 lib.loong_finalize_out.argtypes = [_i64, _i32, _vp, _vp, _i32, _vp]
@@ -219,6 +220,15 @@ def attn_step_bwd(desc: StepDesc, q, k, v, o, d_o, lse, delta, dq, dk, dv, works
     _check(lib.loong_attn_step_bwd(C.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse),
                                    _ptr(delta), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), workspace_bytes,
                                    _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = (64 << 20) + 65536
+
+
+def attn_step_bwd_static(desc: StepDesc, q, k, v, o, d_o, lse, delta, dq, dk, dv, stream=None):
+    """loong_attn_step_bwd_static: the backward step on the library's static scratch array (no workspace)."""
+    _check(lib.loong_attn_step_bwd_static(C.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse),
+                                          _ptr(delta), _ptr(dq), _ptr(dk), _ptr(dv), _stream(stream)))
 
 
 def bwd_delta(desc: StepDesc, o, d_o, delta, stream=None):

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libloong.so")
 
-SOURCES = ["host.cpp", "cost_model.cpp", "elementwise.hip", "device.hip", "layout.hip", "attn_api.hip", "attn_f32.hip", "attn_fwd.hip", "attn_bwd.hip", "attn_bwd_dq.hip"]
+SOURCES = ["host.cpp", "cost_model.cpp", "elementwise.hip", "device.hip", "scratch.hip", "layout.hip", "attn_api.hip", "attn_f32.hip", "attn_fwd.hip", "attn_bwd.hip", "attn_bwd_dq.hip"]
 
 # packed fp32 VALU forms are switched off for every device compile (known-bad on this fleet)
 HIPCC_FLAGS = [
