@@ -36,7 +36,10 @@ HBM_PEAK_GBS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (summaries under profiles/), scaled
 # by the same counters' reading for a copy kernel of known size; null for workloads not profiled.
 TRAFFIC: dict = {
-    "mha7b_32k": 77.7e6,   # 34.1 MiB read + 40.0 MiB written
+    "mha7b_32k": 77.7e6,    # 34.1 MiB read + 40.0 MiB written
+    "gqa7b_128k": 208.3e6,  # 146.6 MiB read + 52.0 MiB written (every step parks partial sums)
+    "long_1m": 557.4e6,     # 497.6 MiB read + 34.0 MiB written (each of the eight L2s streams Q and dO once;
+                            # the diagonal step alone reads 7.25 GiB)
 }
 
 # model dimensions behind the local shapes (LLaMA2-7B: hidden 4096, 32 heads; 8 kv heads for GQA)
