@@ -68,6 +68,15 @@ if not os.path.exists(LIB_PATH):
         f"{LIB_PATH} is missing: build it with `python -m paper_2406_18485_amd.build` "
         "(there is no fallback implementation)")
 
+# One HIP runtime per process: torch ships its own copy and the library must bind to the same one
+# (loaded the other way round, the library pulls in the system's copy first, torch then runs on a
+# runtime it was not built for, and the library's device queries fail).  So torch goes first
+# wherever it is installed; without torch the system's runtime is the only one.
+try:
+    import torch  # noqa: F401
+except ImportError:
+    pass
+
 lib = C.CDLL(LIB_PATH)
 
 _vp, _i32, _i64 = C.c_void_p, C.c_int32, C.c_int64

@@ -16,7 +16,11 @@
 // The E waves run one tile behind the P waves (P of tile t is consumed in the next iteration,
 // from a double-buffered hand-over area; the query tiles stay in LDS for three iterations), so
 // one workgroup barrier per tile suffices and neither role ever waits for the other.  The E
-// waves, which have less element-wise work, also issue the staging loads.
+// waves, which have less element-wise work, also issue the staging loads.  A P wave's own
+// dV += P^T dO of tile t also runs one iteration late, first thing after the barrier, from
+// the P it kept in registers: the iteration then opens with matrix work on one wave of every
+// SIMD while its partner issues the staging loads, instead of both starting with vector and
+// memory instructions (2 % on the kernel, with the operand reads four matrix steps ahead).
 // Splitting the roles halves the registers a wave must hold (so two waves fit a SIMD), and
 // the two waves of a SIMD are in different kinds of work at any time: the vector issue port,
 // which the matrix instructions share with the element-wise ones, is the unit that bounds
@@ -213,7 +217,10 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
   if (it_begin < it_end) issue_tile(cur, 0);
   wait_vmcnt<0>();
 
-  constexpr int PF = 2;  // LDS operands are requested PF matrix steps ahead
+  // P and E = P o T packed, two bf16 per word (elements 2 w, 2 w + 1 of block ib).  A P wave keeps
+  // its P across the barrier: dV += P^T dO of tile t runs at the top of iteration t + 1.
+  uint32_t w2[2][8];
+  constexpr int PF = 4;  // LDS operands are requested PF matrix steps ahead
   // Iteration j: the P waves work on tile j, the E waves on tile j - 1, tile j + 1 is staged.
   int st_p = 0, st_e = 2, st_n = 1;  // LDS stages of those three tiles
   for (int it = it_begin; it <= it_end && it_begin < it_end; ++it) {
@@ -236,10 +243,8 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
     const unsigned char* const xch_r = xch + ((it - it_begin + 1) & 1) * C::XCH_B;  // P of tile it - 1
 
     // Block ib = rows 32 ib .. 32 ib + 31 of the tile; register v of an accumulator is row
-    // acc_row(v, hh) of the block.  pw / ew: P and E = P o T packed, two bf16 per word
-    // (elements 2 w, 2 w + 1).
+    // acc_row(v, hh) of the block.
     floatx16_t st2[2];
-    uint32_t w2[2][8];
     // 2 NKS matrix steps of S (P wave: Q rows, K fragments) or T (E wave: dO rows, -V fragments)
     // of both blocks, block 1 after block 0; `between(k)` is called after step k.
     auto rows_product = [&](const unsigned char* tile, auto&& between) {
@@ -288,6 +293,8 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
       });
     };
 
+    // dV += P^T dO of tile it - 1 (its dO is still staged: the E waves work on that tile now)
+    if (p_wave && it > it_begin) cols_product(smem + st_e * C::STAGE_B + C::QT_B, [](auto) {});
     if (p_active) {
       // exponent offsets -LSE log2 e; masked pairs get -inf: P = 0 whatever the score
       float nl[2][16];
@@ -331,7 +338,6 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
         for (int hf = 0; hf < 2; ++hf)
           *reinterpret_cast<uint4*>(xch_w + (ib * 2 + hf) * 1024) =
               make_uint4(w2[ib][4 * hf], w2[ib][4 * hf + 1], w2[ib][4 * hf + 2], w2[ib][4 * hf + 3]);
-      cols_product(Ot, [](auto) {});  // dV += P^T dO
     } else if (e_active) {
       // T = delta - dO V^T: the chains start from the rows' delta
 #pragma unroll
