@@ -18,7 +18,9 @@ Readings taken where the paper is silent (each is listed in the design notes):
 Pins (tests/test_cost_model.py): the paper's worked size (GQA, 128K tokens, 8 GPUs: 64 MiB per
 step), independence of Size(kv) from d_cp at fixed d_sp, GQA = MHA traffic at d_hp = H,
 zero all-to-all traffic at d_hp = 1, compute-bound and communication-bound limits of
-T_inner_ring, total compute d_cp * T_comp independent of w.
+T_inner_ring, total compute d_cp * T_comp independent of w, and the whole objective with finite
+links worked out by hand on two grids (communication-bound forward with compute-bound backward
+inner ring and an all-to-all; a plain ring without one).
 """
 from __future__ import annotations
 

@@ -68,6 +68,44 @@ def test_objective_reduces_to_compute_when_links_are_infinitely_fast():
     assert math.isclose(t, 8 * 4 * cm.t_comp_fwd(1e-18, 131072, 4096, 4, 8))
 
 
+def test_objective_with_finite_links_worked_by_hand():
+    """The communication terms of the objective, worked out on paper in units of u = 2^-10 s from the formulas of
+    Sec. "Performance Analysis" and the readings the oracle's header lists (a message takes latency + bytes /
+    bandwidth; the backward moves twice the bytes and computes three times as long; the all-to-all runs in the
+    forward and in the backward phase).  S = 1024, D = 64, H = 8, H_kv = 2, alpha = 2^-30.
+
+    Grid d_hp = 4, d_cp = 4, w = 2 (d_sp = 16):
+      Size(kv) = max(2, 4)/8 * 4*1024*64/16 = 8192 B, Size(q) = 2*1024*64/16 = 8192 B,
+      AlltoAll_Volume = (2*8192 + 2*4096) * 3/4 = 18432 B,
+      T_comp^fwd = 2^-30 * 1024^2 * 64 / (4*16) = 1 u, T_comp^bwd = 3 u.
+      latency 0.25 u; inner link 8192 B in 1.25 u; outer link 8192 B in 4 u; all-to-all 18432 B in 1 u.
+      forward:  inner transfer 1.5 u  > 1 u  (communication bound), outer 4.25 u -> A (w-1) + B = 1.5 + 4.25 = 5.75 u
+      backward: inner transfer 0.25 + 2.5 = 2.75 u < 3 u (compute bound), outer 0.25 + 8 = 8.25 u -> 3 + 8.25 = 11.25 u
+      objective = 2 * 1 u + (5.75 + 11.25) u * 4/2 = 36 u.
+    Grid d_hp = 1, d_cp = 4, w = 4 (a plain ring, no all-to-all):
+      Size(kv) = max(2, 1)/8 * 4*1024*64/4 = 16384 B, T_comp^fwd = 2^-30 * 1024^2 * 64 / (4*4) = 4 u, bwd 12 u,
+      forward:  inner 0.25 + 2.5 = 2.75 u < 4 u, outer 0.25 + 8 = 8.25 u -> 3 * 4 + 8.25 = 20.25 u
+      backward: inner 0.25 + 5 = 5.25 u < 12 u, outer 0.25 + 16 = 16.25 u -> 3 * 12 + 16.25 = 52.25 u
+      objective = 72.5 u."""
+    u = 2.0 ** -10
+    link = dict(bw_inner=8192 / (1.25 * u), bw_outer=8192 / (4 * u), bw_alltoall=18432 / u, latency=0.25 * u)
+    assert cm.size_kv(1024, 64, 8, 2, 4, 4) == 8192 and cm.alltoall_volume(1024, 64, 8, 2, 4, 4) == 18432
+    assert math.isclose(cm.objective(2.0 ** -30, 1024, 64, 8, 2, d_hp=4, d_cp=4, w=2, **link), 36 * u, rel_tol=1e-12)
+    assert cm.size_kv(1024, 64, 8, 2, 1, 4) == 16384
+    assert math.isclose(cm.objective(2.0 ** -30, 1024, 64, 8, 2, d_hp=1, d_cp=4, w=4, **link), 72.5 * u, rel_tol=1e-12)
+
+
+def test_calculator_on_the_hand_worked_grids(P):
+    u = 2.0 ** -10
+    link = dict(alpha_fwd=2.0 ** -30, bw_p2p_inner=8192 / (1.25 * u), bw_p2p_outer=8192 / (4 * u), bw_alltoall=18432 / u,
+                latency=0.25 * u)
+    a = P.cost_model(S=1024, D=64, H=8, H_kv=2, d_hp=4, d_cp=4, w=2, **link)
+    assert math.isclose(a["t_inner_ring_fwd"], 5.75 * u, rel_tol=1e-12) and math.isclose(a["t_inner_ring_bwd"], 11.25 * u, rel_tol=1e-12)
+    assert math.isclose(a["t_seq_alltoall"], 2 * u, rel_tol=1e-12) and math.isclose(a["objective"], 36 * u, rel_tol=1e-12)
+    b = P.cost_model(S=1024, D=64, H=8, H_kv=2, d_hp=1, d_cp=4, w=4, **link)
+    assert b["t_seq_alltoall"] == 0.0 and math.isclose(b["objective"], 72.5 * u, rel_tol=1e-12)
+
+
 # ------------------------------------------------------------------ the C calculator against the oracle
 @pytest.fixture(scope="module")
 def P():
