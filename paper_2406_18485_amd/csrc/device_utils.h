@@ -96,14 +96,15 @@ __device__ __forceinline__ float quad_swap2(float x) {
 // 16 (or 4) bytes per lane from global memory straight into LDS: lane l's data lands at
 // lds_addr + 16 l (4 l), lds_addr uniform over the wave.  Written as assembly so that the
 // compiler does not tie every later LDS read to the completion of all loads in flight; the
-// kernels wait for the data they need with wait_vmcnt.
+// kernels wait for the data they need with wait_vmcnt.  The statements clobber "memory": they
+// write LDS behind the compiler's back, so it must not move LDS accesses across them.
 __device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_addr) {
   const uint32_t uniform_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(uniform_addr) : "m0");
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(uniform_addr) : "m0", "memory");
 }
 __device__ __forceinline__ void load_to_lds_4(const void* gptr, uint32_t lds_addr) {
   const uint32_t uniform_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(uniform_addr) : "m0");
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(uniform_addr) : "m0", "memory");
 }
 
 // The same with the address split into a wave-uniform 64-bit base (scalar registers) and a
@@ -115,7 +116,7 @@ __device__ __forceinline__ void load_to_lds_16(const void* uniform_base, uint32_
   const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)a);
   const uint64_t base = ((uint64_t)hi << 32) | (uint64_t)lo;
   const uint32_t uniform_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(uniform_addr) : "m0");
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(uniform_addr) : "m0", "memory");
 }
 
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding)
