@@ -38,6 +38,7 @@ HBM_PEAK_GBS = 8000.0
 TRAFFIC: dict = {
     "mha7b_32k": 77.7e6,    # 34.1 MiB read + 40.0 MiB written
     "gqa7b_128k": 208.3e6,  # 146.6 MiB read + 52.0 MiB written (every step parks partial sums)
+    "dring_256k": 339.0e6,  # 195.3 MiB read + 128.0 MiB written
     "long_1m": 557.4e6,     # 497.6 MiB read + 34.0 MiB written (each of the eight L2s streams Q and dO once;
                             # the diagonal step alone reads 7.25 GiB)
 }
