@@ -253,6 +253,10 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
       };
       bf16x8_t ring[PF + 1];
       static_for<0, PF>([&](auto kc) { ring[kc.value] = operand(kc.value); });
+      // An E wave runs its matrix steps at raised priority: its path from barrier to barrier is the
+      // longer one, and with equal priorities the partner's vector instructions get between its
+      // matrix instructions (1.5 % on the kernel; raising the P waves too, or instead: nothing)
+      if (!p_wave) __builtin_amdgcn_s_setprio(3);
       static_for<0, 2 * NKS>([&](auto kc) {
         constexpr int k = decltype(kc)::value, ib = k / NKS, ks = k % NKS;
         if constexpr (k + PF < 2 * NKS) ring[(k + PF) % (PF + 1)] = operand(k + PF);
@@ -271,6 +275,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
         between(kc);
         __builtin_amdgcn_sched_barrier(0);  // keep the operand reads ahead of their use
       });
+      if (!p_wave) __builtin_amdgcn_s_setprio(0);
     };
     // 4 NDB matrix steps of acc += W^T X over the tile's 64 rows (W = pw or ew, X = dO or Q tile).
     // Element e of the A operand is row 16 sl + 8 (e / 4) + 4 hh + e % 4 of its block, so the
@@ -283,6 +288,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
       };
       bf16x8_t ring[PF + 1];
       static_for<0, PF>([&](auto kc) { ring[kc.value] = operand(kc.value); });
+      if (!p_wave) __builtin_amdgcn_s_setprio(3);
       static_for<0, 4 * NDB>([&](auto kc) {
         constexpr int k = decltype(kc)::value, ib = k / (2 * NDB), sl = (k / NDB) % 2, db = k % NDB;
         if constexpr (k + PF < 4 * NDB) ring[(k + PF) % (PF + 1)] = operand(k + PF);
@@ -291,6 +297,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
         acc[db] = E::mfma(a, ring[k % (PF + 1)], acc[db]);
         __builtin_amdgcn_sched_barrier(0);
       });
+      if (!p_wave) __builtin_amdgcn_s_setprio(0);
     };
 
     // dV += P^T dO of tile it - 1 (its dO is still staged: the E waves work on that tile now)
