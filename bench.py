@@ -425,6 +425,15 @@ def main():
         mfma_sustained = wgs * 4 * iters_probe * 4 * 32768 / (probe_ms * 1e-3) / 1e12
         result["mfma_only_probe_tflops"] = round(mfma_sustained, 1)
         result["pct_of_mfma_only_probe"] = round(100.0 * tflops / mfma_sustained, 2)
+        # the same with operands drawn like the workload's q/k/v (normal * 0.5, bf16): more bits toggle,
+        # the chip holds a lower clock, and that lower rate is what any kernel fed such data can reach
+        gen = torch.Generator(device="cuda:0").manual_seed(7)
+        operands = (torch.randn(1024, device="cuda:0", generator=gen) * 0.5).bfloat16()
+        settle_clock(P, torch, 0.2)
+        probe_ms = timed(lambda: P.mfma_probe(wgs, iters_probe, sink, operands), 3)
+        mfma_random = wgs * 4 * iters_probe * 4 * 32768 / (probe_ms * 1e-3) / 1e12
+        result["mfma_only_probe_workload_values_tflops"] = round(mfma_random, 1)
+        result["pct_of_mfma_only_probe_workload_values"] = round(100.0 * tflops / mfma_random, 2)
 
     cpu_rows = auto_cpu_rows(cfg) if args.cpu_rows < 0 else args.cpu_rows
     if cpu_rows > 0:

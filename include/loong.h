@@ -283,10 +283,15 @@ LOONG_API int loong_cost_search(const loong_cost_in* in, int32_t d_sp, int32_t m
  * every SIMD of the device (`workgroups` x 4 waves x `iters` x 4 instructions).  It writes
  * one float per thread to `sink` (workgroups * 256 floats, device memory) so that the work
  * cannot be dropped.  Timing it gives the matrix-core rate the chip sustains at its real
- * clocks, the second ceiling `bench.py` prints beside the published peak.  FLOPs of a call:
- * workgroups * 4 * iters * 4 * 32768.  Errors: LOONG_E_NULL, LOONG_E_SHAPE (non-positive sizes).
+ * clocks, the second ceiling `bench.py` prints beside the published peak.  That rate depends on
+ * the operand VALUES (the clock the chip holds falls as more bits toggle): with `operands` NULL
+ * the kernel uses nearly constant built-in operands; otherwise `operands` points at 2048 bytes
+ * of device memory, 16-byte aligned, read only: lane l of every wave takes its eight A elements
+ * from bytes [16 l, 16 l + 16) and its eight B elements from bytes [1024 + 16 l, +16), e.g. bf16
+ * values drawn like the workload's.  FLOPs of a call: workgroups * 4 * iters * 4 * 32768.
+ * Errors: LOONG_E_NULL (sink), LOONG_E_ALIGN (operands), LOONG_E_SHAPE (non-positive sizes).
  */
-LOONG_API int loong_mfma_probe(int32_t workgroups, int32_t iters, float* sink, void* stream);
+LOONG_API int loong_mfma_probe(int32_t workgroups, int32_t iters, const void* operands, float* sink, void* stream);
 
 /* Library version, major*10000 + minor*100 + patch. */
 LOONG_API int loong_version(void);

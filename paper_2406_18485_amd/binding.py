@@ -90,7 +90,7 @@ lib.loong_bwd_delta.argtypes = [C.POINTER(StepDesc), _vp, _vp, _vp, _vp]
 lib.loong_init_running.argtypes = [_i64, _i32, _vp, _vp, _vp]
 lib.loong_finalize_out.argtypes = [_i64, _i32, _vp, _vp, _i32, _vp]
 lib.loong_validate_step.argtypes = [C.POINTER(StepDesc)]
-lib.loong_mfma_probe.argtypes = [_i32, _i32, _vp, _vp]
+lib.loong_mfma_probe.argtypes = [_i32, _i32, _vp, _vp, _vp]
 lib.loong_workspace_bytes.argtypes = [C.POINTER(StepDesc), C.POINTER(C.c_int64)]
 lib.loong_permute_rows.argtypes = [C.POINTER(_i64), C.POINTER(_i64), C.POINTER(_i64), _i64, _vp, _vp, _vp]
 lib.loong_reduce_replicas.argtypes = [_i64, _i32, _i64, _vp, _vp, _vp]
@@ -175,8 +175,9 @@ def workspace_bytes(desc) -> int:
     return n.value
 
 
-def mfma_probe(workgroups: int, iters: int, sink, stream=None):
-    _check(lib.loong_mfma_probe(workgroups, iters, _ptr(sink), _stream(stream)))
+def mfma_probe(workgroups: int, iters: int, sink, operands=None, stream=None):
+    """`operands`: None (built-in, nearly constant) or a device tensor of 2048 bytes (see loong_mfma_probe)."""
+    _check(lib.loong_mfma_probe(workgroups, iters, _ptr(operands), _ptr(sink), _stream(stream)))
 
 
 def make_desc(*, batch, n_q_heads, n_kv_heads, head_dim, q_len, kv_len, dtype, softmax_scale,

@@ -236,11 +236,15 @@ int loong_bwd_delta(const loong_step_desc* desc, const void* o, const void* d_o,
 // ---- measurement aid: matrix cores only ---------------------------------------------------
 namespace loong {
 namespace {
-__global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float* sink) {
+__global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, const uint4* operands, float* sink) {
   const int lane = threadIdx.x & 63;
-  // operands that keep the accumulators finite and differ per lane
-  const bf16x8_t a = as_bf16x8(make_uint4(0x3c003c00u + lane, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u));
-  const bf16x8_t b = as_bf16x8(make_uint4(0x38003800u, 0x38003800u + lane, 0x38003800u, 0x38003800u));
+  // built-in operands: nearly constant (few bits change from lane to lane), accumulators stay finite
+  bf16x8_t a = as_bf16x8(make_uint4(0x3c003c00u + lane, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u));
+  bf16x8_t b = as_bf16x8(make_uint4(0x38003800u, 0x38003800u + lane, 0x38003800u, 0x38003800u));
+  if (operands) {  // the caller's values: what the clocks do depends on how many bits toggle
+    a = as_bf16x8(operands[lane]);
+    b = as_bf16x8(operands[64 + lane]);
+  }
   floatx16_t c[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -255,10 +259,12 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float* sink)
 }  // namespace
 }  // namespace loong
 
-extern "C" int loong_mfma_probe(int32_t workgroups, int32_t iters, float* sink, void* stream) {
+extern "C" int loong_mfma_probe(int32_t workgroups, int32_t iters, const void* operands, float* sink, void* stream) {
   loong::clear_error();
   if (!sink) return loong::fail(LOONG_E_NULL, "loong_mfma_probe: NULL sink");
   if (workgroups <= 0 || iters <= 0) return loong::fail(LOONG_E_SHAPE, "loong_mfma_probe: sizes must be positive");
-  loong::mfma_probe_kernel<<<dim3((unsigned)workgroups), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(iters, sink);
+  if (operands && (reinterpret_cast<uintptr_t>(operands) & 15)) return loong::fail(LOONG_E_ALIGN, "loong_mfma_probe: operands must be 16-byte aligned");
+  loong::mfma_probe_kernel<<<dim3((unsigned)workgroups), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+      iters, static_cast<const uint4*>(operands), sink);
   return loong::check_launch("loong_mfma_probe");
 }

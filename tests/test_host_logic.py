@@ -143,8 +143,9 @@ def test_layout_and_probe_entry_points_validate_before_touching_a_device():
     assert lib.loong_reduce_replicas(2, 0, 4, 0x1000, 0x2000, None) == P.E_SHAPE
     assert lib.loong_reduce_replicas(2, 2, 6, 0x1000, 0x2000, None) == P.E_ALIGN
     assert lib.loong_reduce_replicas(0, 2, 4, 0x1000, 0x2000, None) == P.OK
-    assert lib.loong_mfma_probe(0, 1, 0x1000, None) == P.E_SHAPE
-    assert lib.loong_mfma_probe(1, 1, None, None) == P.E_NULL
+    assert lib.loong_mfma_probe(0, 1, None, 0x1000, None) == P.E_SHAPE
+    assert lib.loong_mfma_probe(1, 1, None, None, None) == P.E_NULL
+    assert lib.loong_mfma_probe(1, 1, 0x1008, 0x1000, None) == P.E_ALIGN
 
 
 def test_workspace_bytes_follows_the_split_of_the_query_loops():
