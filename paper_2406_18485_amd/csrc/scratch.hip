@@ -17,7 +17,7 @@ namespace {
 constexpr int64_t kScratchBytes = LOONG_STATIC_SCRATCH_BYTES;
 static_assert(kScratchBytes == loong::kWsHeadBytes + ((int64_t)64 << 20), "header and layout disagree");
 
-__device__ __align__(256) unsigned char scratch[kScratchBytes];
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 constexpr int kMaxDevices = 64;
 // device address of `scratch` on each device, looked up once per device with that device current
