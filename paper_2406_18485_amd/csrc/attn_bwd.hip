@@ -142,6 +142,11 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
       uint4 x = *reinterpret_cast<const uint4*>(row + ks * 16 + hh * 8);
       x.x ^= flip; x.y ^= flip; x.z ^= flip; x.w ^= flip;
       bfrag[ks] = as_bf16x8(x);
+      // K comes with scale * log2 e folded in (rounded to 16 bits again): the score product then ends
+      // in the exponent's units and its chains can start from the rows' offsets, which takes the
+      // multiply-add per element off the vector port (4 % of the kernel).  The second rounding
+      // changes P by less than rounding P itself to 16 bits does.
+      if (p_wave) bfrag[ks] = scaled_fragment<E>(bfrag[ks], p.c);
     }
   }
 
@@ -260,18 +265,7 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
       static_for<0, 2 * NKS>([&](auto kc) {
         constexpr int k = decltype(kc)::value, ib = k / NKS, ks = k % NKS;
         if constexpr (k + PF < 2 * NKS) ring[(k + PF) % (PF + 1)] = operand(k + PF);
-        if constexpr (ks == 0 && true) {
-          if (p_wave) {
-            floatx16_t zero;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) zero[v] = 0.f;
-            st2[ib] = E::mfma(ring[k % (PF + 1)], bfrag[0], zero);
-          } else {
-            st2[ib] = E::mfma(ring[k % (PF + 1)], bfrag[0], st2[ib]);  // C = delta
-          }
-        } else {
-          st2[ib] = E::mfma(ring[k % (PF + 1)], bfrag[ks], st2[ib]);
-        }
+        st2[ib] = E::mfma(ring[k % (PF + 1)], bfrag[ks], st2[ib]);  // the chains start from the exponent offsets (P) or delta (E)
         between(kc);
         __builtin_amdgcn_sched_barrier(0);  // keep the operand reads ahead of their use
       });
@@ -303,8 +297,9 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
     // dV += P^T dO of tile it - 1 (its dO is still staged: the E waves work on that tile now)
     if (p_wave && it > it_begin) cols_product(smem + st_e * C::STAGE_B + C::QT_B, [](auto) {});
     if (p_active) {
-      // exponent offsets -LSE log2 e; masked pairs get -inf: P = 0 whatever the score
-      float nl[2][16];
+      // exponent offsets -LSE log2 e, where the score chains start; masked pairs get -inf: P = 0
+      // whatever the score
+      floatx16_t (&nl)[2] = st2;
 #pragma unroll
       for (int ib = 0; ib < 2; ++ib)
 #pragma unroll
@@ -327,8 +322,8 @@ __global__ __launch_bounds__(kBwdWaves * 64) void bwd_dkv_kernel(const BwdParams
           }
       }
       auto exps = [&](int ib, int w) {  // elements 2 w, 2 w + 1 of block ib
-        const float p0 = fast_exp2(fmaf(st2[ib][2 * w], p.c, nl[ib][2 * w]));
-        const float p1 = fast_exp2(fmaf(st2[ib][2 * w + 1], p.c, nl[ib][2 * w + 1]));
+        const float p0 = fast_exp2(st2[ib][2 * w]);
+        const float p1 = fast_exp2(st2[ib][2 * w + 1]);
         w2[ib][w] = E::pack2(p0, p1);
       };
       // S of both blocks; the exponentials of block 0 between the matrix steps of block 1

@@ -115,7 +115,13 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
     const int64_t ro = b * p.qs[0] + h * p.qs[1] + (int64_t)my_row * p.qs[2];
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
-      qf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(p.q + ro + ks * 16 + hh * 8));
+      // Q comes with the softmax scale and log2 e folded in (and is rounded to 16 bits again): the
+      // score product then ends in the exponent's units and its chain can start from the row's
+      // offset (below).  The second rounding moves a recomputed exponent by about 2^-9 of the
+      // terms' root sum of squares, a relative change of P well below the 2^-9 that rounding P to
+      // 16 bits for the next product costs anyway (the forward pass, whose LSE is compared to
+      // 1e-3, keeps the exact multiply-add).
+      qf[ks] = scaled_fragment<E>(as_bf16x8(*reinterpret_cast<const uint4*>(p.q + ro + ks * 16 + hh * 8)), p.c);
       dof[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(p.d_o + ro + ks * 16 + hh * 8));
     }
     const int64_t r1 = ((int64_t)b * p.Hq + h) * p.q_len + my_row;
@@ -125,8 +131,9 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
   }
 
   floatx16_t ndl;  // -delta of the lane's row in every element: where the dP chains start
+  floatx16_t nlt;  // -LSE log2 e of the lane's row in every element: where the score chains start
 #pragma unroll
-  for (int v = 0; v < 16; ++v) ndl[v] = -dl;
+  for (int v = 0; v < 16; ++v) { ndl[v] = -dl; nlt[v] = nl; }
   floatx16_t acc[NDB];  // dQ^T of the wave's rows (without the softmax scale)
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
@@ -236,28 +243,27 @@ __global__ __launch_bounds__(kRowWaves * 64) void dq_kernel(const DqParams p) {
       // pair of products then waits out a full LDS latency.
       floatx16_t s, dp;
       {
-        constexpr int NIT = 2 * NKS, PF = 6;
+        constexpr int NIT = 2 * NKS, PF = 4;
         auto row_frag = [&](int it) {
           return as_bf16x8(*reinterpret_cast<const uint4*>(((it & 1) ? Vb : Kb) + row_rd[it >> 1]));
         };
         bf16x8_t ring[PF + 1];
         static_for<0, PF>([&](auto i) { ring[i.value] = row_frag(i.value); });
-        floatx16_t zero;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) zero[v] = 0.f;
-        // (the dP chain starts from -delta of the lane's row, so it ends as dP - delta)
+        // (the dP chain starts from -delta of the lane's row, so it ends as dP - delta; the score
+        // chain from -LSE log2 e, so it ends as the exponent of P: two vector instructions per
+        // element that the matrix cores do on the side)
         static_for<0, NIT>([&](auto i) {
           constexpr int it = i.value, ks = it >> 1;
           if constexpr (it + PF < NIT) ring[(it + PF) % (PF + 1)] = row_frag(it + PF);
           __builtin_amdgcn_sched_barrier(0);
           if constexpr (it & 1) dp = E::mfma(ring[it % (PF + 1)], dof[ks], ks ? dp : ndl);
-          else s = E::mfma(ring[it % (PF + 1)], qf[ks], ks ? s : zero);
+          else s = E::mfma(ring[it % (PF + 1)], qf[ks], ks ? s : nlt);
         });
       }
       // ---- dS^T = P^T (dP^T - delta), the softmax scale is applied to the sums at the end
       float e[16];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) e[v] = fast_exp2(fmaf(s[v], p.c, nl)) * dp[v];
+      for (int v = 0; v < 16; ++v) e[v] = fast_exp2(s[v]) * dp[v];
       if (j0 + 32 > klen || (isdiag && j0 + 31 > wrow0)) {  // diagonal or ragged end only
 #pragma unroll
         for (int v = 0; v < 16; ++v) {

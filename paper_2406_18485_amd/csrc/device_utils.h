@@ -67,6 +67,14 @@ struct Fp16 {
   }
 };
 
+// An operand fragment with every element multiplied by c (rounded to the storage type again).
+template <class E>
+__device__ __forceinline__ bf16x8_t scaled_fragment(bf16x8_t f, float c) {
+  const uint4 w = __builtin_bit_cast(uint4, f);
+  return as_bf16x8(make_uint4(E::pack2(E::lo(w.x) * c, E::hi(w.x) * c), E::pack2(E::lo(w.y) * c, E::hi(w.y) * c),
+                              E::pack2(E::lo(w.z) * c, E::hi(w.z) * c), E::pack2(E::lo(w.w) * c, E::hi(w.w) * c)));
+}
+
 // Row index inside a 32x32 accumulator block held in register v of a lane of half hh.
 __device__ __forceinline__ constexpr int acc_row(int v, int hh) { return 8 * (v >> 2) + 4 * hh + (v & 3); }
 
